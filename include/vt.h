@@ -1,0 +1,225 @@
+/*
+ * vt.h - attention over per-request, virtually contiguous KV caches on MI355X (gfx950).
+ *
+ * C ABI of libvt.  Method: "vTensor" (arXiv 2407.15309).  A request's K cache and V cache are each
+ * ONE contiguous virtual address range sized for the maximum sequence length; physical memory is
+ * attached to the range in fixed-size chunks as the sequence grows (paper Section 4.1), so the
+ * attention kernels read plain arrays and need no page-table indirection.
+ *
+ * Conventions shared by every entry point
+ *   - Returns a vt_status: 0 on success, negative on error.  Never throws, never aborts.  A call that
+ *     fails leaves all library state as it was before the call.
+ *   - "device" pointers are GPU addresses valid on the context's device; "host" pointers are ordinary
+ *     process memory.  The library never takes ownership of caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The attention and append
+ *     calls only enqueue work on it; they do not synchronise.  Region calls (reserve / extend /
+ *     release / trim) are host-synchronous driver work and never touch bytes that are already mapped.
+ *   - K/V layout: request b's K region is the row-major array [len_b, n_kv_heads, head_dim] of 16-bit
+ *     elements, token stride n_kv_heads*head_dim elements; V likewise, in a separate region.
+ *   - Query head h uses KV head h / (n_q_heads / n_kv_heads) (grouped-query attention, paper Section
+ *     2.2.3; contiguous groups).
+ *   - A vt_ctx may be used from several threads; region calls are serialised by an internal lock.
+ *     Two attention calls on the same context must not overlap in time (they share one workspace).
+ */
+#ifndef VT_H_
+#define VT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vt_ctx vt_ctx; /* owns the chunk pool (pSet), the VA free-list (vSet), the split-K workspace */
+typedef struct vt_kv vt_kv;   /* one request's K region + V region (one layer); owned by its vt_ctx        */
+
+typedef enum { VT_F16 = 1, VT_BF16 = 2 } vt_dtype;
+
+typedef enum {
+  VT_OK = 0,
+  VT_E_INVALID = -1,     /* bad argument, stale handle, shrink request, empty KV in decode            */
+  VT_E_CAPACITY = -2,    /* length beyond the region's max_tokens                                     */
+  VT_E_OOM = -3,         /* physical budget (max_phys_bytes) or device memory exhausted               */
+  VT_E_DRIVER = -4,      /* a HIP call failed                                                         */
+  VT_E_UNSUPPORTED = -5  /* (dtype, head_dim, group size) combination without a kernel                */
+} vt_status;
+
+typedef struct {
+  void* k_ptr;              /* device base of the K region; constant for the handle's lifetime      */
+  void* v_ptr;              /* device base of the V region                                          */
+  uint64_t len;             /* token rows currently backed and valid                                */
+  uint64_t max_tokens;
+  uint64_t row_bytes;       /* n_kv_heads * head_dim * 2                                            */
+  uint64_t chunk_bytes;
+  uint64_t chunks_mapped;   /* per region (K and V always hold the same count)                      */
+  uint64_t capacity_bytes;  /* per region: round_up(max_tokens*row_bytes, chunk_bytes)              */
+  uint32_t n_kv_heads, head_dim;
+  int32_t dtype;
+  int32_t shared_chunks;    /* leading chunks that alias another request's memory (prefix sharing)  */
+} vt_kv_info;
+
+typedef struct {
+  uint64_t reserved_va_bytes;   /* VA currently reserved from the driver (in use + free-listed)     */
+  uint64_t mapped_bytes;        /* bytes currently mapped into live regions (aliases counted once per mapping) */
+  uint64_t phys_bytes;          /* physical bytes currently held (mapped + pooled chunks)           */
+  uint64_t chunks_created;      /* cumulative driver allocations                                    */
+  uint64_t chunks_reused;       /* cumulative chunks taken from the pool instead                    */
+  uint64_t chunks_pooled;       /* chunks idle in the pool now                                      */
+  uint64_t va_reserved_calls, va_reused, create_calls, map_calls, unmap_calls, release_calls, va_free_calls;
+  uint64_t driver_ns;           /* cumulative host time spent inside driver calls                   */
+  uint64_t live_regions;
+} vt_stats_t;
+
+/* ---- context ------------------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device`.  chunk_bytes: physical chunk size, 0 => 2 MiB (the paper's
+ * "2 MB", Section 4.1); must be a multiple of the device's minimum allocation granularity.
+ * max_phys_bytes: cap on physical bytes held by the context, 0 => no cap.  Paper: Section 4.3, GPU
+ * interface (reserve / create / map). */
+int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_bytes);
+
+/* Same bookkeeping over HOST memory (mmap/memfd stand-ins for reserve/create/map), for tests of the
+ * region logic on machines without a GPU.  Attention calls on such a context return VT_E_UNSUPPORTED;
+ * vt_append copies with memcpy.  chunk_bytes must be a multiple of the host page size. */
+int vt_init_host(vt_ctx** out, uint64_t chunk_bytes, uint64_t max_phys_bytes);
+
+/* Unmaps and frees everything the context holds (all regions, pooled chunks, VA ranges, workspace).
+ * Every vt_kv* of the context is invalid afterwards.  Paper: Section 4.3.2 (vFree, pFree at the end of
+ * serving). */
+int vt_destroy(vt_ctx* ctx);
+
+/* ---- regions (paper Sections 4.3 and 4.4) --------------------------------------------------- */
+
+/* vAlloc: reserves the K and V virtual ranges for one request, sized for max_tokens rows; maps nothing
+ * (len = 0).  A free-listed range of the same size is reused before the driver is asked for a new one.
+ * Paper: Section 4.3.1 vAlloc; Section 4.4 Create. */
+int vt_reserve(vt_ctx* ctx, uint32_t n_kv_heads, uint32_t head_dim, int dtype, uint64_t max_tokens, vt_kv** out);
+
+/* Extend: makes rows [0, new_len) backed, mapping ceil(new_len*row_bytes/chunk) chunks per region, pool
+ * first, then new allocations (pAlloc + Map).  Grow-only: new_len < len => VT_E_INVALID; new_len >
+ * max_tokens => VT_E_CAPACITY; over budget => VT_E_OOM with nothing changed.  Base pointers never move
+ * and mapped bytes are never touched.  Paper: Section 4.3.1 pAlloc / Map; Section 4.4 Extend. */
+int vt_extend(vt_kv* kv, uint64_t new_len_tokens);
+
+/* vt_extend for n requests in one call (one lock, one ABI crossing).  Stops at the first failure and
+ * returns its status; requests before it stay extended, the failing one is unchanged. */
+int vt_extend_batch(vt_kv* const* kvs /*host [n]*/, const uint64_t* new_lens /*host [n]*/, uint32_t n);
+
+/* Prefix Match by aliasing: reserves a new request whose first ceil(n_tokens*row_bytes/chunk) chunks are
+ * the SAME physical chunks as `src`'s (mapped a second time, reference counted; no copy, no new
+ * memory), and sets its len to n_tokens.  n_tokens*row_bytes must be a multiple of chunk_bytes unless
+ * the caller never appends to `dst` (appends beyond n_tokens would otherwise write into the shared
+ * last chunk): a non-aligned n_tokens returns VT_E_INVALID.  Paper: Section 4.4 Prefix Record and
+ * Match; Section 4.2 pSet reference counts. */
+int vt_share_prefix(vt_kv* src, uint64_t n_tokens, uint64_t max_tokens, vt_kv** dst);
+
+/* Release: unmaps the request's chunks into the pool (a shared chunk returns to the pool when its last
+ * mapping goes), puts the VA ranges on the free-list; no device memory is freed (lazy deallocation).
+ * The handle is invalid afterwards.  Paper: Section 4.3.2; Section 4.4 Release. */
+int vt_release(vt_kv* kv);
+
+/* pFree / vFree: really frees pooled chunks beyond `keep_pooled_chunks` and all free-listed VA ranges.
+ * Paper: Section 4.3.2 (explicit memory-emptying). */
+int vt_trim(vt_ctx* ctx, uint64_t keep_pooled_chunks);
+
+int vt_query(const vt_kv* kv, vt_kv_info* out);
+int vt_stats(const vt_ctx* ctx, vt_stats_t* out);
+
+/* KV-cache update: copies n_tokens rows [n_tokens, n_kv_heads, head_dim] from k_rows / v_rows (device
+ * memory; host memory on a host context) into rows [at_token, at_token+n_tokens) of the regions, which
+ * must already be backed (at_token + n_tokens <= len).  Enqueued on `stream`.  Paper: Section 2.1
+ * (decode updates the KV cache). */
+int vt_append(vt_kv* kv, const void* k_rows, const void* v_rows, uint64_t n_tokens, uint64_t at_token, void* stream);
+
+/* One launch that writes one new row per request: row b of k_rows / v_rows (device [batch, n_kv_heads,
+ * head_dim]) goes to token position kv_lens[b]-1 of request b's regions (i.e. call after the lengths
+ * were advanced).  k_ptrs / v_ptrs / kv_lens are the same device arrays vt_attn_decode takes. */
+int vt_append_batch(vt_ctx* ctx, void* const* k_ptrs, void* const* v_ptrs, const int32_t* kv_lens,
+                    const void* k_rows, const void* v_rows, uint32_t batch, uint32_t n_kv_heads, uint32_t head_dim,
+                    void* stream);
+
+/* ---- attention ------------------------------------------------------------------------------ */
+
+typedef struct {
+  int32_t dtype;                 /* vt_dtype of q, out and the K/V regions                            */
+  uint32_t batch, n_q_heads, n_kv_heads, head_dim;
+  float scale;                   /* score scale, normally 1/sqrt(head_dim)                            */
+  const void* q;                 /* device [batch, n_q_heads, head_dim]                               */
+  void* out;                     /* device [batch, n_q_heads, head_dim], same dtype                   */
+  const void* const* k_ptrs;     /* device [batch]: K region base of each request                     */
+  const void* const* v_ptrs;     /* device [batch]: V region base                                     */
+  const int32_t* kv_lens;        /* device [batch]: cached rows to attend over (>= 1)                 */
+  const int32_t* kv_lens_host;   /* host   [batch]: the same values, read for planning                */
+} vt_decode_args;
+
+/* Integer work decomposition of a decode call.  Request b's keys are cut into spans of span_tokens;
+ * split s covers [s*span, min((s+1)*span, len_b)); n_units = sum_b ceil(len_b/span) * n_kv_heads. */
+typedef struct {
+  uint32_t span_tokens;
+  uint32_t max_splits;
+  uint64_t n_units;
+  uint64_t workspace_bytes;
+} vt_plan;
+
+/* Computes the plan vt_attn_decode will use; n_splits_out (host [batch], may be NULL) receives each
+ * request's split count. */
+int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batch, uint32_t n_kv_heads,
+                   uint32_t n_q_heads, uint32_t head_dim, vt_plan* out, int32_t* n_splits_out);
+
+/* Batched decode attention: out[b,h,:] = sum_j softmax_j(scale * <q[b,h,:], K_b[j,g(h),:]>) V_b[j,g(h),:]
+ * over j in [0, kv_lens[b]).  Split-K online softmax with fp32 accumulation followed by a combine pass.
+ * Paper: Section 2.1 (decode stage), Section 6.2.1 (decoding kernel).  The context's workspace is grown
+ * on demand (growing it synchronises the device once; steady-state calls allocate nothing).
+ * Errors: VT_E_INVALID for null pointers, n_q_heads % n_kv_heads != 0 or a host length < 1;
+ * VT_E_UNSUPPORTED unless head_dim is 64 or 128 and n_q_heads/n_kv_heads <= 16. */
+int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* args, void* stream);
+
+typedef struct {
+  int32_t dtype;
+  uint32_t batch, n_q_heads, n_kv_heads, head_dim;
+  float scale;
+  uint32_t total_new_tokens;     /* T = cu_seqlens[batch]                                             */
+  const void* q_new;             /* device [T, n_q_heads, head_dim]; request b owns rows cu[b]..cu[b+1]-1 */
+  void* out;                     /* device [T, n_q_heads, head_dim]                                   */
+  const void* k_new;             /* device [T, n_kv_heads, head_dim], or NULL: the new rows are already */
+  const void* v_new;             /*   in the regions at [prefix_len_b, prefix_len_b + N_b)            */
+  const void* const* k_ptrs;     /* device [batch]                                                    */
+  const void* const* v_ptrs;     /* device [batch]                                                    */
+  const int32_t* cu_seqlens;     /* device [batch+1], cu[0] = 0                                       */
+  const int32_t* prefix_lens;    /* device [batch]: cached rows each request's new tokens fully see   */
+  const int32_t* cu_seqlens_host;   /* host copies of the two arrays above                            */
+  const int32_t* prefix_lens_host;
+} vt_prefill_args;
+
+/* Prefix-prefill attention: new token i of request b (absolute position P_b + i) attends keys
+ * 0 .. P_b + i of concat(cached prefix, new tokens): the whole prefix plus the new tokens causally.
+ * FlashAttention-style tiling on MFMA with fp32 accumulation.  Paper: Section 2.2.2 (prefix cache),
+ * Section 6.2.2 (prefix-prefilling kernel).  Errors as vt_attn_decode; head_dim must be 128 or 64. */
+int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* stream);
+
+/* Pre-sizes the context's workspace so that later attention calls never allocate. */
+int vt_workspace_reserve(vt_ctx* ctx, uint64_t bytes);
+
+/* ---- misc ------------------------------------------------------------------------------------ */
+
+/* Kernel timing for benchmarks.  While enabled, vt_attn_decode brackets its split-pass kernel (which = 0)
+ * and vt_attn_prefix_prefill its main kernel (which = 1) with HIP events recorded on the caller's stream.
+ * vt_profile_collect waits for the events recorded so far, returns their summed elapsed time and count
+ * for `which`, and forgets them.  At most 4096 launches are kept between two collects. */
+int vt_profile_enable(vt_ctx* ctx, int on);
+int vt_profile_collect(vt_ctx* ctx, int which, double* total_ms, uint64_t* launches);
+
+const char* vt_strerror(int status);
+
+/* Tuning knob read by vt_plan_decode / vt_attn_decode: target number of work units (0 => default). */
+int vt_set_plan_target(vt_ctx* ctx, uint64_t target_units);
+
+/* Test hook (host contexts only): the `countdown`-th next driver stand-in call of kind `op`
+ * (0 reserve, 1 create, 2 map, 3 unmap) fails once. */
+int vt_host_fail_after(vt_ctx* ctx, int op, int countdown);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VT_H_ */

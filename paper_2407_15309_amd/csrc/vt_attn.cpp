@@ -1,0 +1,190 @@
+// Host side of the attention entry points: argument checks, the integer split plan, the workspace.
+// Every arithmetic step of attention itself runs in the kernels (vt_decode.hip, vt_prefill.hip).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "vt_internal.h"
+
+namespace vt {
+
+constexpr uint32_t kMinSpan = 128;
+constexpr uint32_t kMaxSpan = 1u << 20;
+constexpr uint64_t kDefaultTargetUnits = 32768;
+
+// Span rule: the smallest power of two >= 128 tokens for which the number of (request, kv head, span)
+// units is at most `target`.  Small problems get short spans (more parallelism), large ones get longer
+// spans (fewer partial results to merge).
+int plan_decode(uint64_t target, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
+                DecodePlan* out, int32_t* n_splits_out) {
+  if (!lens || !out || !hkv || !hq || !d) return VT_E_INVALID;
+  if (target == 0) target = kDefaultTargetUnits;
+  for (uint32_t b = 0; b < batch; ++b)
+    if (lens[b] < 1) return VT_E_INVALID;
+  uint32_t span = kMinSpan;
+  uint64_t total = 0;
+  uint32_t mx = 0;
+  for (;;) {
+    total = 0;
+    mx = 0;
+    for (uint32_t b = 0; b < batch; ++b) {
+      uint32_t n = ((uint32_t)lens[b] + span - 1) / span;
+      total += n;
+      mx = std::max(mx, n);
+    }
+    if (total * hkv <= target || span >= kMaxSpan) break;
+    span *= 2;
+  }
+  out->span = span;
+  out->max_splits = mx;
+  out->n_units = total * hkv;
+  out->ws_bytes = (uint64_t)batch * mx * hq * (d + 2) * sizeof(float);
+  if (n_splits_out)
+    for (uint32_t b = 0; b < batch; ++b) n_splits_out[b] = (int32_t)(((uint32_t)lens[b] + span - 1) / span);
+  return VT_OK;
+}
+
+int ensure_workspace(vt_ctx* ctx, uint64_t bytes) {
+  if (bytes <= ctx->ws_bytes) return VT_OK;
+  if (ctx->be->is_host()) return VT_E_UNSUPPORTED;
+  uint64_t want = std::max<uint64_t>(bytes, 1ull << 20);
+  want = (want + (1ull << 20) - 1) & ~((1ull << 20) - 1);
+  void* p = nullptr;
+  if (hipMalloc(&p, want) != hipSuccess) {
+    (void)hipGetLastError();
+    return VT_E_OOM;
+  }
+  if (ctx->ws) {
+    (void)hipDeviceSynchronize();  // an earlier call may still be using the old buffer
+    (void)hipFree(ctx->ws);
+  }
+  ctx->ws = p;
+  ctx->ws_bytes = want;
+  return VT_OK;
+}
+
+void prof_begin(vt_ctx* ctx, int which, void* stream) {
+  if (!ctx->profile || ctx->prof.size() >= 4096) return;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return;
+  }
+  ctx->prof.push_back(ProfEvent{(void*)a, (void*)b, which});
+  (void)hipEventRecord(a, (hipStream_t)stream);
+}
+
+void prof_end(vt_ctx* ctx, void* stream) {
+  if (!ctx->profile || ctx->prof.empty()) return;
+  (void)hipEventRecord((hipEvent_t)ctx->prof.back().stop, (hipStream_t)stream);
+}
+
+static bool supported_dim(uint32_t d) { return d == 64 || d == 128; }
+
+}  // namespace vt
+
+using namespace vt;
+
+extern "C" {
+
+int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batch, uint32_t n_kv_heads,
+                   uint32_t n_q_heads, uint32_t head_dim, vt_plan* out, int32_t* n_splits_out) {
+  if (!ok_ctx(ctx) || !out) return VT_E_INVALID;
+  DecodePlan p;
+  int rc = plan_decode(ctx->plan_target, kv_lens_host, batch, n_kv_heads, n_q_heads, head_dim, &p, n_splits_out);
+  if (rc != VT_OK) return rc;
+  out->span_tokens = p.span;
+  out->max_splits = p.max_splits;
+  out->n_units = p.n_units;
+  out->workspace_bytes = p.ws_bytes;
+  return VT_OK;
+}
+
+int vt_profile_enable(vt_ctx* ctx, int on) {
+  if (!ok_ctx(ctx)) return VT_E_INVALID;
+  ctx->profile = on != 0;
+  return VT_OK;
+}
+
+int vt_profile_collect(vt_ctx* ctx, int which, double* total_ms, uint64_t* launches) {
+  if (!ok_ctx(ctx) || !total_ms || !launches) return VT_E_INVALID;
+  double sum = 0.0;
+  uint64_t n = 0;
+  std::vector<ProfEvent> keep;
+  int rc = VT_OK;
+  for (auto& e : ctx->prof) {
+    if (e.which != which) {
+      keep.push_back(e);
+      continue;
+    }
+    float ms = 0.f;
+    if (hipEventSynchronize((hipEvent_t)e.stop) == hipSuccess &&
+        hipEventElapsedTime(&ms, (hipEvent_t)e.start, (hipEvent_t)e.stop) == hipSuccess) {
+      sum += ms;
+      ++n;
+    } else {
+      (void)hipGetLastError();
+      rc = VT_E_DRIVER;
+    }
+    (void)hipEventDestroy((hipEvent_t)e.start);
+    (void)hipEventDestroy((hipEvent_t)e.stop);
+  }
+  ctx->prof.swap(keep);
+  *total_ms = sum;
+  *launches = n;
+  return rc;
+}
+
+int vt_workspace_reserve(vt_ctx* ctx, uint64_t bytes) {
+  if (!ok_ctx(ctx)) return VT_E_INVALID;
+  return ensure_workspace(ctx, bytes);
+}
+
+int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
+  if (!ok_ctx(ctx) || !a) return VT_E_INVALID;
+  if (ctx->be->is_host()) return VT_E_UNSUPPORTED;
+  if (a->batch == 0) return VT_OK;
+  if (!a->q || !a->out || !a->k_ptrs || !a->v_ptrs || !a->kv_lens || !a->kv_lens_host) return VT_E_INVALID;
+  if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
+  if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
+  if (!supported_dim(a->head_dim) || a->n_q_heads / a->n_kv_heads > 16) return VT_E_UNSUPPORTED;
+  DecodePlan plan;
+  int rc = plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, &plan,
+                       nullptr);
+  if (rc != VT_OK) return rc;
+  if (plan.max_splits > 65535 || a->batch > 65535) return VT_E_UNSUPPORTED;
+  rc = ensure_workspace(ctx, plan.ws_bytes);
+  if (rc != VT_OK) return rc;
+  return launch_decode(ctx, a, plan, stream);
+}
+
+int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
+  if (!ok_ctx(ctx) || !a) return VT_E_INVALID;
+  if (ctx->be->is_host()) return VT_E_UNSUPPORTED;
+  if (a->batch == 0 || a->total_new_tokens == 0) return VT_OK;
+  if (!a->q_new || !a->out || !a->k_ptrs || !a->v_ptrs || !a->cu_seqlens || !a->prefix_lens || !a->cu_seqlens_host ||
+      !a->prefix_lens_host)
+    return VT_E_INVALID;
+  if ((a->k_new == nullptr) != (a->v_new == nullptr)) return VT_E_INVALID;
+  if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
+  if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
+  if (!supported_dim(a->head_dim)) return VT_E_UNSUPPORTED;
+  if (a->cu_seqlens_host[0] != 0 || (uint32_t)a->cu_seqlens_host[a->batch] != a->total_new_tokens) return VT_E_INVALID;
+  for (uint32_t b = 0; b < a->batch; ++b)
+    if (a->cu_seqlens_host[b + 1] < a->cu_seqlens_host[b] || a->prefix_lens_host[b] < 0) return VT_E_INVALID;
+  return launch_prefill(ctx, a, stream);
+}
+
+int vt_append_batch(vt_ctx* ctx, void* const* k_ptrs, void* const* v_ptrs, const int32_t* kv_lens, const void* k_rows,
+                    const void* v_rows, uint32_t batch, uint32_t n_kv_heads, uint32_t head_dim, void* stream) {
+  if (!ok_ctx(ctx)) return VT_E_INVALID;
+  if (ctx->be->is_host()) return VT_E_UNSUPPORTED;
+  if (batch == 0) return VT_OK;
+  if (!k_ptrs || !v_ptrs || !kv_lens || !k_rows || !v_rows || !n_kv_heads || !head_dim) return VT_E_INVALID;
+  uint64_t row = (uint64_t)n_kv_heads * head_dim * 2;
+  if (row % 16 != 0 || row > (1u << 30)) return VT_E_UNSUPPORTED;
+  return launch_append_batch(k_ptrs, v_ptrs, kv_lens, k_rows, v_rows, batch, (uint32_t)row, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,241 @@
+"""GPU parity of vt_attn_decode (through the C ABI) against the fp64 oracle, plus region behaviour on the
+device: contiguity over scattered chunks, base-pointer stability, bit-identity with plain device memory."""
+
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2407_15309_amd as vt
+import workloads
+from oracle import meta
+from workloads import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import TOL, Regions, dev_bits, host_bits, read_device, run_decode, stream  # noqa: E402
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = vt.vt_init(0, 0, 0)
+    yield c
+    torch.cuda.synchronize()
+    vt.vt_destroy(c)
+
+
+def oracle_decode(cfg, data):
+    q = oracle.widen(data["q"], cfg.dtype)
+    k = [oracle.widen(x, cfg.dtype) for x in data["k"]]
+    v = [oracle.widen(x, cfg.dtype) for x in data["v"]]
+    return oracle.decode(q, k, v, cfg.scale)
+
+
+def check_decode(ctx, cfg, data, tag):
+    say("decode case", tag, "dtype", cfg.dtype, "B", cfg.batch, "Hq/Hkv", cfg.n_q_heads, cfg.n_kv_heads, "D",
+        cfg.head_dim, "lens", data["kv_lens"][:8].tolist(), "seed", data["seed"])
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype)
+    try:
+        got = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, reg.lens, cfg.n_kv_heads, cfg.scale)
+    finally:
+        reg.release()
+    ref = oracle_decode(cfg, data)
+    err = np.abs(oracle.widen(got, cfg.dtype) - ref)
+    say("  max abs err", float(err.max()), "tolerance", TOL[cfg.dtype])
+    assert np.isfinite(oracle.widen(got, cfg.dtype)).all()
+    assert err.max() <= TOL[cfg.dtype]
+    return got
+
+
+def with_lens(cfg, lens, seed=11):
+    """Decode inputs of `cfg`'s shape with the given per-request lengths."""
+    cfg = cfg.replace(batch=len(lens))
+    d = workloads.decode_inputs(cfg, seed=seed)
+    for b, L in enumerate(lens):
+        shp = (L, cfg.n_kv_heads, cfg.head_dim)
+        d["k"][b] = workloads.normal_bits(seed, workloads.gen.T_K, b, shp, cfg.dtype)
+        d["v"][b] = workloads.normal_bits(seed, workloads.gen.T_V, b, shp, cfg.dtype)
+    d["kv_lens"] = np.array(lens, dtype=np.int32)
+    return cfg, d
+
+
+def test_config1_fp16_small(ctx):
+    cfg = CONFIGS[1]
+    check_decode(ctx, cfg, workloads.decode_inputs(cfg), "config1")
+
+
+def test_config2_bf16_mha_full(ctx):
+    cfg = CONFIGS[2]
+    data = workloads.decode_inputs(cfg)
+    assert meta.decode_kv_bytes(data["kv_lens"], 32, 128) > 1.5e9
+    check_decode(ctx, cfg, data, "config2")
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [
+    ("bf16", 32, 8, 128), ("bf16", 64, 8, 128), ("bf16", 32, 2, 128), ("bf16", 32, 4, 128), ("f16", 32, 8, 128),
+    ("bf16", 16, 8, 64), ("f16", 24, 3, 64), ("bf16", 5, 1, 128), ("f16", 6, 6, 128), ("bf16", 14, 7, 64),
+])
+def test_head_group_shapes(ctx, dtype, hq, hkv, d):
+    cfg = CONFIGS[2].replace(dtype=dtype, batch=5, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, kv_len=(1, 700))
+    check_decode(ctx, cfg, workloads.decode_inputs(cfg, seed=1000 + hq * 7 + hkv), "shapes")
+
+
+def test_edge_lengths_around_tiles_and_spans(ctx):
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025]
+    cfg, d = with_lens(CONFIGS[2].replace(n_q_heads=8, n_kv_heads=4), lens)
+    check_decode(ctx, cfg, d, "edges")
+    cfg, d = with_lens(CONFIGS[1], lens[:12], seed=12)
+    check_decode(ctx, cfg, d, "edges-f16-d64")
+
+
+def test_long_request_uses_larger_spans(ctx):
+    """A plan with span > 128 (many units) still matches: shrink the unit target so the span doubles."""
+    cfg, d = with_lens(CONFIGS[2].replace(n_q_heads=16, n_kv_heads=4), [3000, 517, 9000])
+    vt.vt_set_plan_target(ctx, 64)
+    try:
+        plan, ns = vt.vt_plan_decode(ctx, d["kv_lens"], 4, 16, 128)
+        assert plan.span_tokens == meta.decode_plan(d["kv_lens"], 4, 64)[0] > 128
+        check_decode(ctx, cfg, d, "long-span")
+    finally:
+        vt.vt_set_plan_target(ctx, 0)
+
+
+def test_vmm_region_equals_plain_device_memory_bit_for_bit(ctx):
+    """To a kernel a region is an ordinary pointer (paper Section 4.1): same bytes, same result bits."""
+    cfg = CONFIGS[2].replace(batch=6, n_q_heads=32, n_kv_heads=8, kv_len=(300, 3000))
+    data = workloads.decode_inputs(cfg, seed=77)
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype)
+    try:
+        a = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, reg.lens, cfg.n_kv_heads, cfg.scale)
+    finally:
+        reg.release()
+    kt = [dev_bits(x) for x in data["k"]]
+    vt_ = [dev_bits(x) for x in data["v"]]
+    kp = torch.tensor([t.data_ptr() for t in kt], dtype=torch.int64).cuda()
+    vp = torch.tensor([t.data_ptr() for t in vt_], dtype=torch.int64).cuda()
+    b = run_decode(ctx, cfg.dtype, data["q"], kp, vp, data["kv_lens"], cfg.n_kv_heads, cfg.scale)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_region_is_contiguous_over_scattered_chunks_on_device(ctx):
+    hkv, d = 8, 128                                      # 2 KiB rows, 1024 rows per 2 MiB chunk
+    a = vt.vt_reserve(ctx, hkv, d, vt.VT_BF16, 8192)
+    vt.vt_extend(a, 5 * 1024)
+    vt.vt_release(a)                                     # 10 chunks into the pool
+    b = vt.vt_reserve(ctx, hkv, d, vt.VT_BF16, 8192)
+    L = 3 * 1024 + 7
+    vt.vt_extend(b, L)                                   # 4 + 4 chunks, pool first
+    info = vt.vt_query(b)
+    assert info.chunks_mapped == meta.chunks_for_len(L, hkv, d) == 4
+    assert info.k_ptr % (2 << 20) == 0 and info.capacity_bytes == meta.capacity_bytes(8192, hkv, d)
+    rng = np.random.default_rng(3)
+    rows = rng.integers(0, 65535, size=(L, hkv, d), dtype=np.uint16)
+    rows_v = rng.integers(0, 65535, size=(L, hkv, d), dtype=np.uint16)
+    vt.vt_append(b, dev_bits(rows), dev_bits(rows_v), L, 0, stream())
+    np.testing.assert_array_equal(read_device(info.k_ptr, L * 2048).view(np.uint16).reshape(L, hkv, d), rows)
+    np.testing.assert_array_equal(read_device(info.v_ptr, L * 2048).view(np.uint16).reshape(L, hkv, d), rows_v)
+    vt.vt_release(b)
+
+
+def test_extend_changes_no_prior_output_and_never_moves_the_base(ctx):
+    """Appending via vt_extend leaves decode over the old length bit-identical, also when the extension is
+    issued while a decode kernel over the old rows is still in flight (paper Section 4.4, Extend)."""
+    cfg = CONFIGS[2].replace(batch=4, n_q_heads=32, n_kv_heads=8, kv_len=(900, 1100))
+    data = workloads.decode_inputs(cfg, seed=5)
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=4096)
+    try:
+        old = reg.lens.copy()
+        k0, v0 = reg.k_ptrs.clone(), reg.v_ptrs.clone()
+        before = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, old, cfg.n_kv_heads, cfg.scale)
+        # launch again and extend across a chunk boundary while it runs
+        q = dev_bits(data["q"])
+        out = torch.zeros_like(q)
+        lens_dev = torch.from_numpy(old).cuda()
+        args = vt.make_decode_args(vt.VT_BF16, cfg.batch, 32, 8, 128, cfg.scale, q, out, reg.k_ptrs, reg.v_ptrs,
+                                   lens_dev, old)
+        vt.vt_attn_decode(ctx, args, stream())
+        vt.vt_extend_batch(reg.kvs, [int(x) + 1500 for x in old])
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host_bits(out), before)
+        reg.refresh()
+        assert torch.equal(reg.k_ptrs, k0) and torch.equal(reg.v_ptrs, v0)
+        for kv, L in zip(reg.kvs, old):
+            info = vt.vt_query(kv)
+            assert info.len == L + 1500 and info.chunks_mapped == meta.chunks_for_len(int(L) + 1500, 8, 128)
+        after = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, old, cfg.n_kv_heads, cfg.scale)
+        np.testing.assert_array_equal(after, before)
+    finally:
+        reg.release()
+
+
+def test_decode_invariants_on_gpu(ctx):
+    """Key permutation leaves the output unchanged within tolerance; identical V rows return that row."""
+    cfg = CONFIGS[2].replace(batch=2, n_q_heads=8, n_kv_heads=2, kv_len=(200, 400))
+    data = workloads.decode_inputs(cfg, seed=9)
+    a = check_decode(ctx, cfg, data, "perm-base")
+    rng = np.random.default_rng(1)
+    perm = [rng.permutation(len(x)) for x in data["k"]]
+    data2 = dict(data, k=[x[p] for x, p in zip(data["k"], perm)], v=[x[p] for x, p in zip(data["v"], perm)])
+    b = check_decode(ctx, cfg, data2, "perm-shuffled")
+    assert np.abs(oracle.widen(a, "bf16") - oracle.widen(b, "bf16")).max() <= TOL["bf16"]
+    row = workloads.normal_bits(3, 4, 0, (1, 2, 128), "bf16")
+    data3 = dict(data, v=[np.broadcast_to(row, x.shape).copy() for x in data["v"]])
+    c = check_decode(ctx, cfg, data3, "same-v-rows")
+    want = np.repeat(oracle.widen(row[0], "bf16"), 4, axis=0)
+    assert np.abs(oracle.widen(c, "bf16") - want[None]).max() <= 2.0 ** -7 * np.abs(want).max()
+
+
+def test_bad_arguments_are_refused(ctx):
+    q = torch.zeros(1, 8, 128, dtype=torch.int16).cuda()
+    lens = np.array([4], np.int32)
+    ok = dict(dtype=vt.VT_BF16, batch=1, n_q_heads=8, n_kv_heads=8, head_dim=128, scale=0.1, q=q, out=q, k_ptrs=q,
+              v_ptrs=q, kv_lens=q, kv_lens_host=lens)
+    for change, status in ((dict(n_kv_heads=3), vt.VT_E_INVALID), (dict(head_dim=96), vt.VT_E_UNSUPPORTED),
+                           (dict(q=None), vt.VT_E_INVALID), (dict(dtype=9), vt.VT_E_INVALID),
+                           (dict(n_q_heads=136, n_kv_heads=8), vt.VT_E_UNSUPPORTED),
+                           (dict(kv_lens_host=np.array([0], np.int32)), vt.VT_E_INVALID)):
+        with pytest.raises(vt.VtError) as e:
+            vt.vt_attn_decode(ctx, vt.make_decode_args(**dict(ok, **change)), stream())
+        assert e.value.status == status, change
+
+
+def test_steady_state_decode_steps_with_extend_and_append(ctx):
+    """Config-5-shaped loop at reduced batch: each step extends every request by one token, appends the new
+    K/V rows with one launch, then decodes over the extended cache; metadata is checked every step."""
+    cfg = CONFIGS[5].replace(batch=6, kv_len=(1000, 1030), steps=40)
+    data = workloads.decode_inputs(cfg)
+    k = [oracle.widen(x, cfg.dtype) for x in data["k"]]
+    v = [oracle.widen(x, cfg.dtype) for x in data["v"]]
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=8192 + cfg.steps)
+    try:
+        k0 = reg.k_ptrs.clone()
+        lens = reg.lens.copy()
+        for step in range(cfg.steps):
+            si = workloads.step_inputs(cfg, step)
+            lens = lens + 1
+            vt.vt_extend_batch(reg.kvs, lens.tolist())
+            lens_dev = torch.from_numpy(lens).cuda()
+            vt.vt_append_batch(ctx, reg.k_ptrs, reg.v_ptrs, lens_dev, dev_bits(si["k_row"]), dev_bits(si["v_row"]),
+                               cfg.batch, cfg.n_kv_heads, cfg.head_dim, stream())
+            got = run_decode(ctx, cfg.dtype, si["q"], reg.k_ptrs, reg.v_ptrs, lens, cfg.n_kv_heads, cfg.scale,
+                             lens_dev)
+            for b in range(cfg.batch):
+                k[b] = np.concatenate([k[b], oracle.widen(si["k_row"][b], cfg.dtype)[None]])
+                v[b] = np.concatenate([v[b], oracle.widen(si["v_row"][b], cfg.dtype)[None]])
+                info = vt.vt_query(reg.kvs[b])
+                assert info.len == lens[b] and info.chunks_mapped == meta.chunks_for_len(int(lens[b]), 8, 128)
+            ref = oracle.decode(oracle.widen(si["q"], cfg.dtype), k, v, cfg.scale)
+            err = np.abs(oracle.widen(got, cfg.dtype) - ref).max()
+            assert err <= TOL[cfg.dtype], (step, err)
+        assert torch.equal(reg.k_ptrs, k0)
+        say("steady-state", cfg.steps, "steps ok; chunk crossings:",
+            sum(int(meta.chunks_for_len(int(L), 8, 128) > meta.chunks_for_len(int(L) - cfg.steps, 8, 128)) for L in lens))
+    finally:
+        reg.release()
