@@ -1,0 +1,209 @@
+"""GPU parity of vt_attn_prefix_prefill (through the C ABI) against the fp64 oracle, and the multi-turn
+scenario: prefix-prefill, then extend + append the new turn, then one decode step over the grown cache."""
+
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2407_15309_amd as vt
+import workloads
+from oracle import meta
+from workloads import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import TOL, Regions, dev_bits, run_decode, run_prefill, stream  # noqa: E402
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = vt.vt_init(0, 0, 0)
+    yield c
+    torch.cuda.synchronize()
+    vt.vt_destroy(c)
+
+
+def oracle_prefill(cfg, d):
+    w = lambda x: oracle.widen(x, cfg.dtype)
+    return oracle.prefix_prefill(w(d["q_new"]), w(d["k_new"]), w(d["v_new"]), d["cu_seqlens"],
+                                 [w(x) for x in d["k"]], [w(x) for x in d["v"]], cfg.scale)
+
+
+def check_prefill(ctx, cfg, d, tag, new_in_cache=False):
+    say("prefill case", tag, "dtype", cfg.dtype, "B", cfg.batch, "Hq/Hkv", cfg.n_q_heads, cfg.n_kv_heads, "D",
+        cfg.head_dim, "P", d["prefix_lens"][:8].tolist(), "N", d["new_lens"][:8].tolist(), "seed", d["seed"],
+        "new_in_cache", new_in_cache)
+    if new_in_cache:
+        cu = d["cu_seqlens"]
+        k = [np.concatenate([d["k"][b], d["k_new"][cu[b]:cu[b + 1]]]) for b in range(cfg.batch)]
+        v = [np.concatenate([d["v"][b], d["v_new"][cu[b]:cu[b + 1]]]) for b in range(cfg.batch)]
+    else:
+        k, v = d["k"], d["v"]
+    reg = Regions(ctx, k, v, cfg.dtype, headroom=1)
+    try:
+        got = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale, new_in_cache)
+    finally:
+        reg.release()
+    ref = oracle_prefill(cfg, d)
+    gv = oracle.widen(got, cfg.dtype)
+    assert np.isfinite(gv).all()
+    err = np.abs(gv - ref)
+    say("  max abs err", float(err.max()), "tolerance", TOL[cfg.dtype])
+    assert err.max() <= TOL[cfg.dtype]
+    return got
+
+
+def with_lens(cfg, plens, nlens, seed=21):
+    cfg = cfg.replace(batch=len(plens))
+    d = workloads.prefill_inputs(cfg.replace(kv_len=(1, 2), new_len=(1, 2)), seed=seed)
+    g = workloads.gen
+    d["prefix_lens"] = np.array(plens, np.int32)
+    d["new_lens"] = np.array(nlens, np.int32)
+    d["cu_seqlens"] = np.concatenate([[0], np.cumsum(nlens)]).astype(np.int32)
+    kv = lambda t, b, n: workloads.normal_bits(seed, t, b, (n, cfg.n_kv_heads, cfg.head_dim), cfg.dtype)
+    d["k"] = [kv(g.T_K, b, p) for b, p in enumerate(plens)]
+    d["v"] = [kv(g.T_V, b, p) for b, p in enumerate(plens)]
+    d["k_new"] = np.concatenate([kv(g.T_KNEW, b, n) for b, n in enumerate(nlens)])
+    d["v_new"] = np.concatenate([kv(g.T_VNEW, b, n) for b, n in enumerate(nlens)])
+    d["q_new"] = np.concatenate([workloads.normal_bits(seed, g.T_QNEW, b, (n, cfg.n_q_heads, cfg.head_dim), cfg.dtype)
+                                 for b, n in enumerate(nlens)])
+    return cfg, d
+
+
+def test_small_gqa_bf16(ctx):
+    cfg = CONFIGS[3].replace(batch=3, kv_len=(100, 700), new_len=(1, 200))
+    check_prefill(ctx, cfg, workloads.prefill_inputs(cfg, seed=31), "small")
+
+
+def test_config3_full(ctx):
+    cfg = CONFIGS[3]
+    d = workloads.prefill_inputs(cfg)
+    assert meta.prefill_flops(d["prefix_lens"], d["new_lens"], 32, 128) > 1e11
+    check_prefill(ctx, cfg, d, "config3")
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [
+    ("bf16", 8, 8, 128), ("bf16", 16, 2, 128), ("bf16", 56, 8, 128), ("f16", 32, 8, 128), ("f16", 8, 2, 64),
+    ("bf16", 32, 1, 128), ("bf16", 12, 4, 64), ("f16", 3, 3, 128),
+])
+def test_head_group_shapes(ctx, dtype, hq, hkv, d):
+    cfg = CONFIGS[3].replace(dtype=dtype, batch=3, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, kv_len=(0, 300),
+                             new_len=(1, 300))
+    check_prefill(ctx, cfg, workloads.prefill_inputs(cfg, seed=500 + hq * 3 + hkv), "shapes")
+
+
+def test_edge_lengths(ctx):
+    """No prefix (plain causal attention), single new token (= decode), lengths around the tile sizes."""
+    plens = [0, 0, 1, 63, 64, 65, 127, 500, 0, 300, 129]
+    nlens = [1, 130, 1, 64, 65, 63, 1, 1, 64, 257, 128]
+    cfg, d = with_lens(CONFIGS[3], plens, nlens)
+    check_prefill(ctx, cfg, d, "edges")
+    cfg, d = with_lens(CONFIGS[3].replace(dtype="f16", n_q_heads=4, n_kv_heads=4, head_dim=64), plens, nlens, seed=22)
+    check_prefill(ctx, cfg, d, "edges-mha-f16-d64")
+
+
+def test_empty_request_in_batch(ctx):
+    cfg, d = with_lens(CONFIGS[3], [50, 70, 10], [5, 0, 9])
+    check_prefill(ctx, cfg, d, "empty-request")
+
+
+def test_new_rows_already_in_cache_gives_identical_bits(ctx):
+    cfg = CONFIGS[3].replace(batch=3, kv_len=(100, 700), new_len=(30, 200))
+    d = workloads.prefill_inputs(cfg, seed=41)
+    a = check_prefill(ctx, cfg, d, "split-sources", new_in_cache=False)
+    b = check_prefill(ctx, cfg, d, "in-cache", new_in_cache=True)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_causality_on_gpu(ctx):
+    """Dropping the last new token changes no earlier output row (bitwise)."""
+    cfg, d = with_lens(CONFIGS[3], [200], [90], seed=23)
+    full = check_prefill(ctx, cfg, d, "causal-full")
+    cfg2, d2 = with_lens(CONFIGS[3], [200], [89], seed=23)
+    np.testing.assert_array_equal(d2["q_new"], d["q_new"][:89])
+    part = check_prefill(ctx, cfg2, d2, "causal-part")
+    np.testing.assert_array_equal(full[:89], part)
+
+
+def sampled_rows_check(cfg, d, got, rows_per_request=3):
+    """Oracle on sampled new tokens: row i equals decode with q_i over the first P+i+1 keys."""
+    w = lambda x: oracle.widen(x, cfg.dtype)
+    cu = d["cu_seqlens"]
+    worst = 0.0
+    for b in range(cfg.batch):
+        n, P = int(d["new_lens"][b]), int(d["prefix_lens"][b])
+        kc = np.concatenate([w(d["k"][b]), w(d["k_new"][cu[b]:cu[b + 1]])])
+        vc = np.concatenate([w(d["v"][b]), w(d["v_new"][cu[b]:cu[b + 1]])])
+        for i in sorted({0, n // 2, n - 1})[:rows_per_request]:
+            ref = oracle.decode(w(d["q_new"][cu[b] + i])[None], [kc[: P + i + 1]], [vc[: P + i + 1]], cfg.scale)[0]
+            worst = max(worst, float(np.abs(w(got[cu[b] + i]) - ref).max()))
+    return worst
+
+
+def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
+    """Config 4 at full size: prefix-prefill over 8K-32K token histories (checked on sampled rows, all heads),
+    then vt_extend grows each request by its new turn, the rows are appended, and one decode step runs over
+    the extended cache (checked on every output)."""
+    cfg = CONFIGS[4]
+    d = workloads.prefill_inputs(cfg, threads=16)
+    say("config4: P", d["prefix_lens"].tolist(), "N", d["new_lens"].tolist())
+    reg = Regions(ctx, d["k"], d["v"], cfg.dtype, max_tokens=cfg.kv_len[1] + cfg.new_len[1] + 1)
+    try:
+        base = reg.k_ptrs.clone()
+        got = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale)
+        assert np.isfinite(oracle.widen(got, cfg.dtype)).all()
+        err = sampled_rows_check(cfg, d, got)
+        say("  prefill sampled rows max abs err", err)
+        assert err <= TOL[cfg.dtype]
+        # grow every request by its new turn and write the rows
+        cu = d["cu_seqlens"]
+        new_total = (d["prefix_lens"] + d["new_lens"]).astype(np.int64)
+        vt.vt_extend_batch(reg.kvs, new_total.tolist())
+        for b, kv in enumerate(reg.kvs):
+            vt.vt_append(kv, dev_bits(d["k_new"][cu[b]:cu[b + 1]]), dev_bits(d["v_new"][cu[b]:cu[b + 1]]),
+                         int(d["new_lens"][b]), int(d["prefix_lens"][b]), stream())
+            info = vt.vt_query(kv)
+            assert info.len == new_total[b]
+            assert info.chunks_mapped == meta.chunks_for_len(int(new_total[b]), cfg.n_kv_heads, cfg.head_dim)
+        torch.cuda.synchronize()
+        reg.refresh()
+        assert torch.equal(reg.k_ptrs, base)
+        # one decode step over the extended cache
+        q = np.stack([workloads.normal_bits(d["seed"], workloads.gen.T_STEP_Q, b, (cfg.n_q_heads, cfg.head_dim),
+                                            cfg.dtype) for b in range(cfg.batch)])
+        out = run_decode(ctx, cfg.dtype, q, reg.k_ptrs, reg.v_ptrs, reg.lens, cfg.n_kv_heads, cfg.scale)
+        w = lambda x: oracle.widen(x, cfg.dtype)
+        kc = [np.concatenate([w(d["k"][b]), w(d["k_new"][cu[b]:cu[b + 1]])]) for b in range(cfg.batch)]
+        vc = [np.concatenate([w(d["v"][b]), w(d["v_new"][cu[b]:cu[b + 1]])]) for b in range(cfg.batch)]
+        ref = oracle.decode(w(q), kc, vc, cfg.scale)
+        derr = float(np.abs(w(out) - ref).max())
+        say("  decode after extend max abs err", derr)
+        assert derr <= TOL[cfg.dtype]
+        # the prefill in "rows already in cache" mode now sees the same keys: identical bits
+        again = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale, new_in_cache=True)
+        np.testing.assert_array_equal(again, got)
+    finally:
+        reg.release()
+
+
+def test_bad_arguments_are_refused(ctx):
+    t = torch.zeros(4, 8, 128, dtype=torch.int16).cuda()
+    cu, pl = np.array([0, 4], np.int32), np.array([3], np.int32)
+    ok = dict(dtype=vt.VT_BF16, batch=1, n_q_heads=8, n_kv_heads=8, head_dim=128, scale=0.1, total_new_tokens=4,
+              q_new=t, out=t, k_new=t, v_new=t, k_ptrs=t, v_ptrs=t, cu_seqlens=t, prefix_lens=t, cu_seqlens_host=cu,
+              prefix_lens_host=pl)
+    for change, status in ((dict(v_new=None), vt.VT_E_INVALID), (dict(head_dim=80), vt.VT_E_UNSUPPORTED),
+                           (dict(total_new_tokens=5), vt.VT_E_INVALID), (dict(n_kv_heads=5), vt.VT_E_INVALID),
+                           (dict(prefix_lens_host=np.array([-1], np.int32)), vt.VT_E_INVALID),
+                           (dict(out=None), vt.VT_E_INVALID)):
+        with pytest.raises(vt.VtError) as e:
+            vt.vt_attn_prefix_prefill(ctx, vt.make_prefill_args(**dict(ok, **change)), stream())
+        assert e.value.status == status, change
