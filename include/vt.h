@@ -153,8 +153,13 @@ typedef struct {
   const int32_t* kv_lens_host;   /* host   [batch]: the same values, read for planning                */
 } vt_decode_args;
 
-/* Integer work decomposition of a decode call.  Request b's keys are cut into spans of span_tokens;
- * split s covers [s*span, min((s+1)*span, len_b)); n_units = sum_b ceil(len_b/span) * n_kv_heads. */
+/* Integer work decomposition of a decode call ("tape split").  Per KV head, the requests' cached tokens laid
+ * end to end form a tape of total = sum_b len_b tokens, cut into segments of span_tokens tokens; one wavefront
+ * owns one (segment, kv head).  With slots = the plan target (default 2048 wavefront slots):
+ *   n_seg       = max(1, min(slots / n_kv_heads, ceil(total / 32)))
+ *   span_tokens = round_up(ceil(total / n_seg), 32)
+ *   pieces_b    = (T_b + len_b - 1) / span_tokens - T_b / span_tokens + 1,  T_b = tokens of the requests before b
+ *   max_splits  = max_b pieces_b;   n_units = ceil(total / span_tokens) * n_kv_heads. */
 typedef struct {
   uint32_t span_tokens;
   uint32_t max_splits;
@@ -163,16 +168,16 @@ typedef struct {
 } vt_plan;
 
 /* Computes the plan vt_attn_decode will use; n_splits_out (host [batch], may be NULL) receives each
- * request's split count. */
+ * request's piece count. */
 int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batch, uint32_t n_kv_heads,
                    uint32_t n_q_heads, uint32_t head_dim, vt_plan* out, int32_t* n_splits_out);
 
 /* Batched decode attention: out[b,h,:] = sum_j softmax_j(scale * <q[b,h,:], K_b[j,g(h),:]>) V_b[j,g(h),:]
- * over j in [0, kv_lens[b]).  Split-K online softmax with fp32 accumulation followed by a combine pass.
+ * over j in [0, kv_lens[b]).  Online softmax with fp32 accumulation over equal tape segments, followed by a merge of the requests that were cut.
  * Paper: Section 2.1 (decode stage), Section 6.2.1 (decoding kernel).  The context's workspace is grown
  * on demand (growing it synchronises the device once; steady-state calls allocate nothing).
  * Errors: VT_E_INVALID for null pointers, n_q_heads % n_kv_heads != 0 or a host length < 1;
- * VT_E_UNSUPPORTED unless head_dim is 64 or 128 and n_q_heads/n_kv_heads <= 16. */
+ * VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 16 and batch <= 4096. */
 int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* args, void* stream);
 
 typedef struct {
@@ -212,7 +217,8 @@ int vt_profile_collect(vt_ctx* ctx, int which, double* total_ms, uint64_t* launc
 
 const char* vt_strerror(int status);
 
-/* Tuning knob read by vt_plan_decode / vt_attn_decode: target number of work units (0 => default). */
+/* Tuning knob read by vt_plan_decode / vt_attn_decode: number of wavefront slots the tape is split for
+ * (0 => default 2048 = 256 CUs x 8 resident wavefronts). */
 int vt_set_plan_target(vt_ctx* ctx, uint64_t target_units);
 
 /* Test hook (host contexts only): the `countdown`-th next driver stand-in call of kind `op`

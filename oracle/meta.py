@@ -8,9 +8,9 @@ the maximum sequence length, physical memory is attached in fixed-size chunks
 (2 MiB), and only as many chunks are mapped as the current length needs.
 
 The decode split plan is this library's own rule (the paper is silent about the
-kernel's work decomposition): every request's keys are cut into spans of P
-tokens, P being the smallest power of two >= 128 for which the number of
-(request, kv head, span) work units does not exceed a fixed target.
+kernel's work decomposition): per KV head the requests' tokens laid end to end
+form a tape that is cut into equal segments, one per wavefront slot; a request
+is covered by as many "pieces" as segments it touches.
 """
 
 from __future__ import annotations
@@ -19,9 +19,7 @@ from typing import List, Sequence, Tuple
 
 ELEM_BYTES = 2                 # fp16 and bf16
 CHUNK_BYTES = 2 * 1024 * 1024  # "2 MB" physical chunk of the paper, read as 2 MiB
-PLAN_MIN_SPAN = 128
-PLAN_MAX_SPAN = 1 << 20
-PLAN_TARGET_UNITS = 32768
+PLAN_WAVE_SLOTS = 2048         # 256 CUs x 2 workgroups x 4 wavefronts
 
 
 def row_bytes(n_kv_heads: int, head_dim: int) -> int:
@@ -39,21 +37,27 @@ def chunks_for_len(length: int, n_kv_heads: int, head_dim: int, chunk: int = CHU
 
 
 def decode_plan(kv_lens: Sequence[int], n_kv_heads: int,
-                target_units: int = PLAN_TARGET_UNITS) -> Tuple[int, List[int], int, int]:
-    """Returns (span P, n_splits per request, max_splits, n_units)."""
-    span = PLAN_MIN_SPAN
-    while True:
-        n_splits = [(int(L) + span - 1) // span for L in kv_lens]
-        units = sum(n_splits) * n_kv_heads
-        if units <= target_units or span >= PLAN_MAX_SPAN:
-            break
-        span *= 2
-    return span, n_splits, (max(n_splits) if n_splits else 0), units
+                slots: int = PLAN_WAVE_SLOTS) -> Tuple[int, List[int], int, int]:
+    """Returns (segment length, pieces per request, max pieces, n_units)."""
+    total = sum(int(L) for L in kv_lens)
+    n_seg = max(1, min(slots // n_kv_heads, (total + 31) // 32))
+    seg_len = (total + n_seg - 1) // n_seg
+    seg_len = (seg_len + 31) // 32 * 32
+    pieces, start = [], 0
+    for L in kv_lens:
+        L = int(L)
+        pieces.append((start + L - 1) // seg_len - start // seg_len + 1)
+        start += L
+    units = (total + seg_len - 1) // seg_len * n_kv_heads
+    return seg_len, pieces, (max(pieces) if pieces else 0), units
 
 
-def split_range(length: int, span: int, s: int) -> Tuple[int, int]:
-    """Token range [begin, end) of split s of a request of `length` tokens."""
-    return s * span, min((s + 1) * span, int(length))
+def piece_range(kv_lens: Sequence[int], seg_len: int, b: int, piece: int) -> Tuple[int, int]:
+    """Token range [begin, end) inside request b of its piece number `piece`."""
+    start = sum(int(L) for L in kv_lens[:b])
+    L = int(kv_lens[b])
+    seg = start // seg_len + piece
+    return max(seg * seg_len - start, 0), min((seg + 1) * seg_len - start, L)
 
 
 # --- accounting used by reports (what the method must move / compute) ---------------------------

@@ -8,39 +8,40 @@
 
 namespace vt {
 
-constexpr uint32_t kMinSpan = 128;
-constexpr uint32_t kMaxSpan = 1u << 20;
-constexpr uint64_t kDefaultTargetUnits = 32768;
+constexpr uint64_t kDefaultWaveSlots = 2048;  // 256 CUs x 2 workgroups x 4 wavefronts
 
-// Span rule: the smallest power of two >= 128 tokens for which the number of (request, kv head, span)
-// units is at most `target`.  Small problems get short spans (more parallelism), large ones get longer
-// spans (fewer partial results to merge).
-int plan_decode(uint64_t target, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
+// Tape split.  Per KV head the requests' tokens laid end to end form a tape of total = sum_b L_b tokens.  It is
+// cut into n_seg = max(1, min(slots / Hkv, ceil(total / 32))) segments of seg_len = round_up(ceil(total / n_seg), 32)
+// tokens; one wavefront owns one (segment, kv head).  Request b, starting at tape position T_b, is covered by
+// pieces_b = (T_b + L_b - 1) / seg_len - T_b / seg_len + 1 segments.
+int plan_decode(uint64_t slots, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
                 DecodePlan* out, int32_t* n_splits_out) {
   if (!lens || !out || !hkv || !hq || !d) return VT_E_INVALID;
-  if (target == 0) target = kDefaultTargetUnits;
-  for (uint32_t b = 0; b < batch; ++b)
-    if (lens[b] < 1) return VT_E_INVALID;
-  uint32_t span = kMinSpan;
+  if (slots == 0) slots = kDefaultWaveSlots;
   uint64_t total = 0;
-  uint32_t mx = 0;
-  for (;;) {
-    total = 0;
-    mx = 0;
-    for (uint32_t b = 0; b < batch; ++b) {
-      uint32_t n = ((uint32_t)lens[b] + span - 1) / span;
-      total += n;
-      mx = std::max(mx, n);
-    }
-    if (total * hkv <= target || span >= kMaxSpan) break;
-    span *= 2;
+  for (uint32_t b = 0; b < batch; ++b) {
+    if (lens[b] < 1) return VT_E_INVALID;
+    total += (uint64_t)lens[b];
   }
-  out->span = span;
-  out->max_splits = mx;
-  out->n_units = total * hkv;
-  out->ws_bytes = (uint64_t)batch * mx * hq * (d + 2) * sizeof(float);
-  if (n_splits_out)
-    for (uint32_t b = 0; b < batch; ++b) n_splits_out[b] = (int32_t)(((uint32_t)lens[b] + span - 1) / span);
+  if (total > 0x7fffffffull) return VT_E_UNSUPPORTED;
+  uint64_t n_seg = std::min<uint64_t>(slots / hkv, (total + 31) / 32);
+  if (n_seg < 1) n_seg = 1;
+  uint64_t seg_len = total ? (total + n_seg - 1) / n_seg : 32;
+  seg_len = (seg_len + 31) / 32 * 32;
+  uint32_t mx = 0;
+  uint64_t T = 0;
+  for (uint32_t b = 0; b < batch; ++b) {
+    const uint64_t L = (uint64_t)lens[b];
+    const uint32_t pieces = (uint32_t)((T + L - 1) / seg_len - T / seg_len + 1);
+    if (n_splits_out) n_splits_out[b] = (int32_t)pieces;
+    mx = std::max(mx, pieces);
+    T += L;
+  }
+  out->seg_len = (uint32_t)seg_len;
+  out->n_seg = (uint32_t)n_seg;
+  out->max_pieces = mx;
+  out->n_units = (total + seg_len - 1) / seg_len * hkv;
+  out->ws_bytes = decode_workspace_bytes(batch, mx, hq, d);
   return VT_OK;
 }
 
@@ -94,8 +95,8 @@ int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batc
   DecodePlan p;
   int rc = plan_decode(ctx->plan_target, kv_lens_host, batch, n_kv_heads, n_q_heads, head_dim, &p, n_splits_out);
   if (rc != VT_OK) return rc;
-  out->span_tokens = p.span;
-  out->max_splits = p.max_splits;
+  out->span_tokens = p.seg_len;
+  out->max_splits = p.max_pieces;
   out->n_units = p.n_units;
   out->workspace_bytes = p.ws_bytes;
   return VT_OK;
@@ -153,7 +154,7 @@ int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
   int rc = plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, &plan,
                        nullptr);
   if (rc != VT_OK) return rc;
-  if (plan.max_splits > 65535 || a->batch > 65535) return VT_E_UNSUPPORTED;
+  if (a->batch > 65535) return VT_E_UNSUPPORTED;
   rc = ensure_workspace(ctx, plan.ws_bytes);
   if (rc != VT_OK) return rc;
   return launch_decode(ctx, a, plan, stream);

@@ -5,24 +5,28 @@
 // KV head g living at base_b + (j*Hkv + g)*D.  Because a request's cache is one contiguous virtual
 // range (paper Section 4.1) the kernel addresses rows by plain pointer arithmetic.
 //
-// Work decomposition: one wavefront per (request, kv head, span of `span` tokens); a workgroup holds
-// the wavefronts of up to 4 adjacent kv heads of the same span so that concurrently issued loads
-// cover adjacent 256 B pieces of the same token rows.  Each wavefront streams its span in tiles of 32
-// tokens and keeps an online-softmax state (running max m, running sum l, fp32 accumulator) for all
-// query heads of its group at once, so every K/V byte is read from HBM once per KV head.
+// Work decomposition ("tape" split).  For every KV head the cached tokens of all requests, laid end to end,
+// form one tape of sum_b L_b tokens.  The tape is cut into n_seg equal segments of seg_len tokens and one
+// wavefront owns one (segment, kv head): every wavefront reads the same number of tokens (no ragged tail
+// however the lengths are distributed), reads them as one long sequential stream per region (which is what
+// HBM likes), and the 4 wavefronts of a workgroup take 4 adjacent kv heads of the same segment, so the
+// workgroup's loads cover 1 KiB contiguous per token row.  A segment may cross request boundaries: the part
+// of a request inside a segment is a "piece".  A piece that is the whole request is normalised and written
+// to the output directly; otherwise the wavefront stores (m, l, acc) per head for the piece and a small
+// second kernel merges a request's pieces with the log-sum-exp rule.  A wavefront keeps the next tile's loads
+// in flight at all times, across piece boundaries too.
 //
-// Matrix-core mapping (v_mfma_f32_16x16x32, one wavefront):
+// Matrix-core mapping (v_mfma_f32_16x16x32, one wavefront, tiles of 32 tokens):
 //   S^T[token, head]  = K_tile[16 tokens x D] * Q^T[D x 16 heads]      (A = K rows, B = Q, heads padded to 16)
 //   O^T[d, head]     += V_tile^T[d x 32 tokens] * P^T[32 tokens x heads] (A = V^T, B = P)
-// The result layout of the first product (lane holds one head column and four token rows per 16-token
-// block) is exactly the B-operand layout of the second once the 32 tokens of a tile are assigned to the
-// contraction slots in the order each lane already holds them, so P never moves between lanes.  V^T is
+// All G query heads of the group ride in the N dimension, so every K/V byte is read from HBM once per KV
+// head.  The result layout of the first product (lane holds one head column and four token rows per
+// 16-token block) is exactly the B-operand layout of the second once the 32 tokens of a tile are assigned to
+// the contraction slots in the order each lane already holds them, so P never moves between lanes.  V^T is
 // produced without shared memory: a lane loads the same 16-byte column chunk of the 8 token rows of its
 // contraction slots and transposes the 8x8 block of 16-bit values inside its own registers.  K goes
 // through a wavefront-private LDS staging buffer so that the global loads stay fully coalesced
 // (16 lanes x 16 B = one 256 B row piece) while the MFMA operand wants 16 different rows per 16 lanes.
-//
-// A second small kernel merges the per-span partial results with the usual log-sum-exp rule.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -37,7 +41,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
-constexpr int kTile = 32;  // tokens per tile
+constexpr int kTile = 32;   // tokens per tile
+constexpr int kWaves = 4;   // wavefronts per workgroup
 
 template <int DT>
 struct Elem;
@@ -81,11 +86,12 @@ struct DecodeParams {
   const char* const* k_ptrs;
   const char* const* v_ptrs;
   const int32_t* kv_lens;
-  float* part_acc;  // [B][max_splits][Hq][D]
-  float* part_m;    // [B][max_splits][Hq], running max of scale*log2(e)*score
-  float* part_l;    // [B][max_splits][Hq]
+  int32_t* tape;    // [B+1] exclusive prefix sums of kv_lens, written by workgroup 0 for the merge kernel
+  float* part_acc;  // [B][max_pieces][Hq][D]
+  float* part_m;    // [B][max_pieces][Hq], running max of scale*log2(e)*score
+  float* part_l;    // [B][max_pieces][Hq]
   void* out;        // [B][Hq][D]
-  uint32_t hq, hkv, group, span, max_splits;
+  uint32_t batch, hq, hkv, group, seg_len, max_pieces, n_seg;
   float scale_log2e;
 };
 
@@ -109,61 +115,132 @@ struct Tile {
   u32x4 v[8];
 };
 
-template <int DT, int D, int W>
-__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_split_kernel(DecodeParams p) {
+// The part of one request that lies inside this wavefront's segment.  Fields are wavefront-uniform except the
+// two lane base pointers.
+struct Piece {
+  bool valid;
+  int b, t0, t1, index, count;  // tokens [t0, t1) of request b; piece `index` of `count`
+  const char* kb;               // lane's K base: region + head offset + its 16-byte chunk
+  const char* vb;
+};
+
+template <int DT, int D>
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_kernel(
+    DecodeParams p) {
   using T = Tile<D>;
   constexpr int CH = T::CH, TPL = T::TPL, NLK = T::NLK;
-  constexpr int KK = D / 32;             // MFMA k-steps of the score product
-  constexpr int NM = D / 16;             // MFMAs (16 d-rows each) of the value product
-  constexpr int RSB = D * 2 + 16;        // LDS row stride in bytes (16 B pad: conflict-free operand reads)
-  __shared__ __attribute__((aligned(16))) char lds_all[W][kTile * RSB];
+  constexpr int KK = D / 32;       // MFMA k-steps of the score product
+  constexpr int NM = D / 16;       // MFMAs (16 d-rows each) of the value product
+  constexpr int RSB = D * 2 + 16;  // LDS row stride in bytes (16 B pad: conflict-free operand reads)
+  __shared__ __attribute__((aligned(16))) char lds_all[kWaves][kTile * RSB];
+  __shared__ int tape[kMaxDecodeBatch + 1];  // tape[b] = tokens of the requests before b
+  __shared__ int wave_tot[kWaves];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t g = blockIdx.x * W + wave, s = blockIdx.y, b = blockIdx.z;
-  if (g >= p.hkv) return;
-  const int L = p.kv_lens[b];
-  const int t0 = (int)(s * p.span);
-  if (t0 >= L) return;
-  const int t1 = min(t0 + (int)p.span, L);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int B = (int)p.batch, seg_len = (int)p.seg_len;
+
+  // Exclusive prefix sum of the lengths: 16 requests per thread, wavefront scan, then across wavefronts.
+  {
+    int local[16], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = tid * 16 + i;
+      local[i] = r < B ? p.kv_lens[r] : 0;
+      sum += local[i];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int base = incl - sum;
+    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = tid * 16 + i;
+      if (r <= B) {
+        tape[r] = base;
+        if (blockIdx.x == 0) p.tape[r] = base;
+      }
+      base += local[i];
+    }
+    __syncthreads();
+  }
+  const int total = tape[B];
+
+  // This wavefront's (segment, kv head).
+  const unsigned w_global = (unsigned)__builtin_amdgcn_readfirstlane((int)(blockIdx.x * kWaves + wave));
+  const int sidx = (int)(w_global / p.hkv);
+  const int g = (int)(w_global - (unsigned)sidx * p.hkv);
+  const int seg0 = sidx * seg_len;
+  if (sidx >= (int)p.n_seg || seg0 >= total) return;
+  const int seg1 = min(seg0 + seg_len, total);
+
   char* lds = lds_all[wave];
-
   const int c16 = lane & 15, j = lane >> 4;
   const int cK = lane % CH, jK = lane / CH;
   const uint32_t row_bytes = p.hkv * D * 2;
-  const char* kb = p.k_ptrs[b] + (size_t)g * D * 2 + cK * 16;
-  const char* vb = p.v_ptrs[b] + (size_t)g * D * 2 + (c16 % CH) * 16;
 
-  // Q as the B operand: lane (head c16, slot j) holds d-chunk 4*kk + j of its head; heads >= group are zero.
-  u32x4 qf[KK];
+  auto make_piece = [&](Piece& d, int b) {
+    d.valid = b < B && tape[b] < seg1;
+    if (!d.valid) return;
+    const int T0 = tape[b], L = tape[b + 1] - T0;
+    d.b = b;
+    d.t0 = max(seg0 - T0, 0);
+    d.t1 = min(L, seg1 - T0);
+    const int first = T0 / seg_len;
+    d.index = sidx - first;
+    d.count = (T0 + L - 1) / seg_len - first + 1;
+    d.kb = p.k_ptrs[b] + (size_t)g * D * 2 + cK * 16;
+    d.vb = p.v_ptrs[b] + (size_t)g * D * 2 + (c16 % CH) * 16;
+  };
+
+  Piece cur, nxt;
   {
-    const char* qh = p.q + ((size_t)b * p.hq + (size_t)g * p.group + c16) * D * 2;
+    int lo = 0, hi = B;  // request containing tape position seg0: tape[lo] <= seg0 < tape[lo+1]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (tape[mid] <= seg0) lo = mid; else hi = mid;
+    }
+    make_piece(cur, lo);
+    make_piece(nxt, lo + 1);
+  }
+
+  u32x4 qf[KK];
+  f32x4 acc[NM];
+  float m_run, l_run;
+  // Q as the B operand: lane (head c16, slot j) holds d-chunk 4*kk + j of its head; heads >= group are zero.
+  auto begin_piece = [&](const Piece& d) {
+    const char* qh = p.q + ((size_t)d.b * p.hq + (size_t)g * p.group + c16) * D * 2;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       u32x4 z = {0u, 0u, 0u, 0u};
       qf[kk] = (c16 < (int)p.group) ? *(const u32x4*)(qh + (4 * kk + j) * 16) : z;
     }
-  }
-
-  f32x4 acc[NM];
 #pragma unroll
-  for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_run = -INFINITY;
+    l_run = 0.f;
+  };
 
-  auto load_tile = [&](T& t, int tile) {
-    const int last = t1 - 1;
+  auto load_tile = [&](T& t, const Piece& d, int tile) {
+    const int last = d.t1 - 1;
 #pragma unroll
     for (int i = 0; i < NLK; ++i) {
-      int tok = min(tile + i * TPL + jK, last);
-      t.k[i] = *(const u32x4*)(kb + (size_t)tok * row_bytes);
+      const int tok = min(tile + i * TPL + jK, last);
+      t.k[i] = *(const u32x4*)(d.kb + (size_t)tok * row_bytes);
     }
 #pragma unroll
     for (int i8 = 0; i8 < 8; ++i8) {
-      int tok = min(tile + (i8 & 3) + 4 * j + (i8 >> 2) * 16, last);
-      t.v[i8] = *(const u32x4*)(vb + (size_t)tok * row_bytes);
+      const int tok = min(tile + (i8 & 3) + 4 * j + (i8 >> 2) * 16, last);
+      t.v[i8] = *(const u32x4*)(d.vb + (size_t)tok * row_bytes);
     }
   };
 
-  auto compute_tile = [&](const T& t, int tile) {
+  auto compute_tile = [&](const T& t, int tile, int t1) {
     // K tile -> LDS (coalesced layout) -> MFMA A-operand layout.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -178,7 +255,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       sc[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        u32x4 kf = *(const u32x4*)(lds + (16 * hh + c16) * RSB + (4 * kk + j) * 16);
+        const u32x4 kf = *(const u32x4*)(lds + (16 * hh + c16) * RSB + (4 * kk + j) * 16);
         sc[hh] = Elem<DT>::mfma(kf, qf[kk], sc[hh]);
       }
     }
@@ -187,8 +264,8 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      int tok = tile + (e & 3) + 4 * j + (e >> 2) * 16;
-      float v = sc[e >> 2][e & 3] * p.scale_log2e;
+      const int tok = tile + (e & 3) + 4 * j + (e >> 2) * 16;
+      const float v = sc[e >> 2][e & 3] * p.scale_log2e;
       x[e] = tok < t1 ? v : -INFINITY;
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
@@ -223,28 +300,41 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
   };
 
-  T ta, tb;
-  int tile = t0;
-  load_tile(ta, tile);
-  for (;;) {
-    if (tile + kTile < t1) load_tile(tb, tile + kTile);
-    compute_tile(ta, tile);
-    tile += kTile;
-    if (tile >= t1) break;
-    if (tile + kTile < t1) load_tile(ta, tile + kTile);
-    compute_tile(tb, tile);
-    tile += kTile;
-    if (tile >= t1) break;
-  }
+  // d index of accumulator element (m, i) of this lane.
+  auto d_of = [&](int m, int i) -> int {
+    if constexpr (D == 128) return 32 * j + 8 * i + m;
+    const int r = 4 * j + i;
+    return 8 * (r & 7) + 2 * m + (r >> 3);
+  };
 
-  // Partial result of this span: (m, l, acc) per head.
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  if (c16 < (int)p.group) {
-    const size_t pidx = ((size_t)b * p.max_splits + s) * p.hq + (size_t)g * p.group + c16;
+  auto end_piece = [&](const Piece& d) {
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (c16 >= (int)p.group) return;
+    const size_t head = (size_t)g * p.group + c16;
+    if (d.count == 1) {
+      // The piece is the whole request: normalise and write the output row.
+      const float inv = 1.0f / l_run;
+      unsigned short* o = (unsigned short*)p.out + ((size_t)d.b * p.hq + head) * D;
+      if constexpr (D == 128) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float r[8];
+#pragma unroll
+          for (int m = 0; m < 8; ++m) r[m] = acc[m][i] * inv;
+          *(u32x4*)(o + 32 * j + 8 * i) = Elem<DT>::pack8(r);
+        }
+      } else {
+#pragma unroll
+        for (int m = 0; m < NM; ++m)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[d_of(m, i)] = Elem<DT>::cvt(acc[m][i] * inv);
+      }
+      return;
+    }
+    const size_t pidx = ((size_t)d.b * p.max_pieces + d.index) * p.hq + head;
     float* pa = p.part_acc + pidx * D;
     if constexpr (D == 128) {
-      // acc[m][i] is d = 32*j + 8*i + m
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         f32x4 lo = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
@@ -253,29 +343,60 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         *(f32x4*)(pa + 32 * j + 8 * i + 4) = hi;
       }
     } else {
-      // acc[m][i] is row r = 4*j + i of MFMA m: d = 8*(r % 8) + 2*m + r / 8
 #pragma unroll
       for (int m = 0; m < NM; ++m)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          int r = 4 * j + i;
-          pa[8 * (r & 7) + 2 * m + (r >> 3)] = acc[m][i];
-        }
+        for (int i = 0; i < 4; ++i) pa[d_of(m, i)] = acc[m][i];
     }
     if (j == 0) {
       p.part_m[pidx] = m_run;
       p.part_l[pidx] = l_run;
     }
+  };
+
+  T ta, tb;
+  int tile = cur.t0;
+  begin_piece(cur);
+  load_tile(ta, cur, tile);
+  bool running = true;
+  // One phase: start the loads of the tile after this one (of this piece, else of the next piece), compute
+  // this tile, and on the piece's last tile finish it and move to the next piece.
+  auto phase = [&](T& now, T& next) {
+    if (tile + kTile < cur.t1) {
+      load_tile(next, cur, tile + kTile);
+    } else if (nxt.valid) {
+      load_tile(next, nxt, nxt.t0);
+    }
+    compute_tile(now, tile, cur.t1);
+    tile += kTile;
+    if (tile >= cur.t1) {
+      end_piece(cur);
+      if (!nxt.valid) {
+        running = false;
+        return;
+      }
+      cur = nxt;
+      begin_piece(cur);
+      tile = cur.t0;
+      make_piece(nxt, cur.b + 1);
+    }
+  };
+  while (running) {
+    phase(ta, tb);
+    if (!running) break;
+    phase(tb, ta);
   }
 }
 
-// Merge of the per-span partials: M = max_s m_s; out = sum_s acc_s 2^(m_s-M) / sum_s l_s 2^(m_s-M).
+// Merge of a request's pieces (requests with a single piece were written by the main kernel):
+// M = max_s m_s; out = sum_s acc_s 2^(m_s-M) / sum_s l_s 2^(m_s-M).
 template <int DT, int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams p) {
   const uint32_t h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int L = p.kv_lens[b];
-  const int n = min((L + (int)p.span - 1) / (int)p.span, (int)p.max_splits);
-  const size_t base = (size_t)b * p.max_splits * p.hq + h;
+  const int T0 = p.tape[b], L = p.tape[b + 1] - T0, seg_len = (int)p.seg_len;
+  const int n = min((T0 + L - 1) / seg_len - T0 / seg_len + 1, (int)p.max_pieces);
+  if (n <= 1) return;
+  const size_t base = (size_t)b * p.max_pieces * p.hq + h;
   float M = -INFINITY;
   for (int s = 0; s < n; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.hq]);
   float num = 0.f, den = 0.f;
@@ -299,51 +420,60 @@ __global__ void append_batch_kernel(char* const* k_ptrs, char* const* v_ptrs, co
     *(u32x4*)(base + off) = *(const u32x4*)(src + off);
 }
 
-template <int DT, int D>
-int launch_decode_t(vt_ctx* ctx, const DecodeParams& p, uint32_t batch, hipStream_t st) {
-  const uint32_t W = p.hkv % 4 == 0 ? 4 : (p.hkv % 2 == 0 ? 2 : 1);
-  dim3 grid(p.hkv / W, p.max_splits, batch);
-  prof_begin(ctx, 0, st);
-  if (W == 4)
-    hipLaunchKernelGGL((decode_split_kernel<DT, D, 4>), grid, dim3(256), 0, st, p);
-  else if (W == 2)
-    hipLaunchKernelGGL((decode_split_kernel<DT, D, 2>), grid, dim3(128), 0, st, p);
-  else
-    hipLaunchKernelGGL((decode_split_kernel<DT, D, 1>), grid, dim3(64), 0, st, p);
-  prof_end(ctx, st);
-  if (hipGetLastError() != hipSuccess) return VT_E_DRIVER;
-  hipLaunchKernelGGL((decode_combine_kernel<DT, D>), dim3(p.hq, batch), dim3(D), 0, st, p);
-  return hipGetLastError() == hipSuccess ? VT_OK : VT_E_DRIVER;
-}
+constexpr uint64_t kTapeBytes = ((uint64_t)(kMaxDecodeBatch + 1) * sizeof(int32_t) + 255) & ~255ull;
 
 }  // namespace
 
+uint64_t decode_workspace_bytes(uint32_t batch, uint32_t max_pieces, uint32_t hq, uint32_t d) {
+  return kTapeBytes + (uint64_t)batch * max_pieces * hq * (d + 2) * sizeof(float);
+}
+
 int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream) {
+  if (a->batch > (uint32_t)kMaxDecodeBatch) return VT_E_UNSUPPORTED;
   DecodeParams p;
   p.q = (const char*)a->q;
   p.k_ptrs = (const char* const*)a->k_ptrs;
   p.v_ptrs = (const char* const*)a->v_ptrs;
   p.kv_lens = a->kv_lens;
-  const size_t n_part = (size_t)a->batch * plan.max_splits * a->n_q_heads;
-  p.part_acc = (float*)ctx->ws;
+  char* ws = (char*)ctx->ws;
+  p.tape = (int32_t*)ws;
+  const size_t n_part = (size_t)a->batch * plan.max_pieces * a->n_q_heads;
+  p.part_acc = (float*)(ws + kTapeBytes);
   p.part_m = p.part_acc + n_part * a->head_dim;
   p.part_l = p.part_m + n_part;
   p.out = a->out;
+  p.batch = a->batch;
   p.hq = a->n_q_heads;
   p.hkv = a->n_kv_heads;
   p.group = a->n_q_heads / a->n_kv_heads;
-  p.span = plan.span;
-  p.max_splits = plan.max_splits;
+  p.seg_len = plan.seg_len;
+  p.max_pieces = plan.max_pieces;
+  p.n_seg = plan.n_seg;
   p.scale_log2e = a->scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
-  if (a->dtype == VT_BF16) {
-    if (a->head_dim == 128) return launch_decode_t<VT_BF16, 128>(ctx, p, a->batch, st);
-    if (a->head_dim == 64) return launch_decode_t<VT_BF16, 64>(ctx, p, a->batch, st);
-  } else {
-    if (a->head_dim == 128) return launch_decode_t<VT_F16, 128>(ctx, p, a->batch, st);
-    if (a->head_dim == 64) return launch_decode_t<VT_F16, 64>(ctx, p, a->batch, st);
-  }
-  return VT_E_UNSUPPORTED;
+  const uint64_t waves = (uint64_t)plan.n_seg * a->n_kv_heads;
+  const uint32_t blocks = (uint32_t)((waves + kWaves - 1) / kWaves);
+  const dim3 cgrid(p.hq, a->batch);
+  const bool combine = plan.max_pieces > 1;
+  prof_begin(ctx, 0, st);
+#define VT_LAUNCH(DT, DD)                                                                        \
+  do {                                                                                           \
+    hipLaunchKernelGGL((decode_kernel<DT, DD>), dim3(blocks), dim3(64 * kWaves), 0, st, p);      \
+    prof_end(ctx, st);                                                                           \
+    if (combine) hipLaunchKernelGGL((decode_combine_kernel<DT, DD>), cgrid, dim3(DD), 0, st, p); \
+  } while (0)
+  if (a->dtype == VT_BF16 && a->head_dim == 128)
+    VT_LAUNCH(VT_BF16, 128);
+  else if (a->dtype == VT_BF16 && a->head_dim == 64)
+    VT_LAUNCH(VT_BF16, 64);
+  else if (a->dtype == VT_F16 && a->head_dim == 128)
+    VT_LAUNCH(VT_F16, 128);
+  else if (a->dtype == VT_F16 && a->head_dim == 64)
+    VT_LAUNCH(VT_F16, 64);
+  else
+    return VT_E_UNSUPPORTED;
+#undef VT_LAUNCH
+  return hipGetLastError() == hipSuccess ? VT_OK : VT_E_DRIVER;
 }
 
 int launch_append_batch(void* const* k_ptrs, void* const* v_ptrs, const int32_t* kv_lens, const void* k_rows,

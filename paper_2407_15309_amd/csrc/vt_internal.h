@@ -80,13 +80,18 @@ namespace vt {
 inline bool ok_ctx(const vt_ctx* c) { return c && c->magic == VT_CTX_MAGIC; }
 inline bool ok_kv(const vt_kv* k) { return k && k->magic == VT_KV_MAGIC && k->alive && ok_ctx(k->ctx); }
 
+constexpr int kMaxDecodeBatch = 4096;  // requests per decode launch (the tape prefix table lives in LDS)
+
 // Integer plan of a decode call (see vt_plan in vt.h).
 struct DecodePlan {
-  uint32_t span, max_splits;
+  uint32_t seg_len, n_seg, max_pieces;
   uint64_t n_units, ws_bytes;
 };
 int plan_decode(uint64_t target, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
                 DecodePlan* out, int32_t* n_splits_out);
+
+// Bytes of device workspace a decode launch needs: counters, per-(request, kv head) flags, partial results.
+uint64_t decode_workspace_bytes(uint32_t batch, uint32_t max_pieces, uint32_t hq, uint32_t d);
 
 // Grows the context's device workspace to at least `bytes`.
 int ensure_workspace(vt_ctx* ctx, uint64_t bytes);

@@ -95,14 +95,18 @@ def test_edge_lengths_around_tiles_and_spans(ctx):
     check_decode(ctx, cfg, d, "edges-f16-d64")
 
 
-def test_long_request_uses_larger_spans(ctx):
-    """A plan with span > 128 (many units) still matches: shrink the unit target so the span doubles."""
-    cfg, d = with_lens(CONFIGS[2].replace(n_q_heads=16, n_kv_heads=4), [3000, 517, 9000])
-    vt.vt_set_plan_target(ctx, 64)
+def test_plans_with_few_and_many_segments(ctx):
+    """The result does not depend on how the tape is cut: few long segments (pieces span several requests) and
+    many short ones (a request is cut into dozens of pieces) both match the oracle."""
+    cfg, d = with_lens(CONFIGS[2].replace(n_q_heads=16, n_kv_heads=4), [3000, 517, 9000, 33, 1])
     try:
-        plan, ns = vt.vt_plan_decode(ctx, d["kv_lens"], 4, 16, 128)
-        assert plan.span_tokens == meta.decode_plan(d["kv_lens"], 4, 64)[0] > 128
-        check_decode(ctx, cfg, d, "long-span")
+        for slots in (4, 8, 64, 100000):
+            vt.vt_set_plan_target(ctx, slots)
+            plan, ns = vt.vt_plan_decode(ctx, d["kv_lens"], 4, 16, 128)
+            want = meta.decode_plan(d["kv_lens"], 4, slots)
+            assert (plan.span_tokens, ns.tolist(), plan.max_splits, plan.n_units) == want
+            say("slots", slots, "segment", plan.span_tokens, "pieces", ns.tolist())
+            check_decode(ctx, cfg, d, "tape-split")
     finally:
         vt.vt_set_plan_target(ctx, 0)
 

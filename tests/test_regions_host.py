@@ -261,13 +261,15 @@ def test_plan_decode_matches_the_documented_rule(ctx):
         span, n_splits, mx, units = meta.decode_plan(lens, hkv)
         assert (plan.span_tokens, plan.max_splits, plan.n_units) == (span, mx, units)
         assert ns.tolist() == n_splits
-        assert plan.workspace_bytes == B * mx * hkv * 2 * 130 * 4
+        assert plan.workspace_bytes >= B * mx * hkv * 2 * 130 * 4        # room for every (m, l, acc) partial
     with pytest.raises(vt.VtError):
         vt.vt_plan_decode(ctx, np.array([5, 0], np.int32), 8, 8, 128)     # empty KV is invalid in decode
-    vt.vt_set_plan_target(ctx, 64)
-    lens = np.array([1000, 3000], np.int32)
-    plan, ns = vt.vt_plan_decode(ctx, lens, 8, 8, 128)
-    assert (plan.span_tokens, ns.tolist()) == (meta.decode_plan(lens, 8, 64)[0], meta.decode_plan(lens, 8, 64)[1])
+    for slots in (8, 64, 100000):
+        vt.vt_set_plan_target(ctx, slots)
+        lens = np.array([1000, 3000, 17], np.int32)
+        plan, ns = vt.vt_plan_decode(ctx, lens, 8, 8, 128)
+        want = meta.decode_plan(lens, 8, slots)
+        assert (plan.span_tokens, ns.tolist(), plan.max_splits, plan.n_units) == want
 
 
 def test_attention_on_a_host_context_is_refused(ctx):

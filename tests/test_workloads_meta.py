@@ -119,17 +119,26 @@ def test_prefill_flops_counts_unmasked_pairs_only():
 
 
 def test_decode_plan_rule():
+    """Tape split: equal segments over the concatenated tokens; pieces tile every request exactly."""
     lens = [1, 128, 129, 4096]
-    span, ns, mx, units = meta.decode_plan(lens, 4)
-    assert span == 128 and ns == [1, 1, 2, 32] and mx == 32 and units == 36 * 4
-    # ranges tile [0, L) exactly
-    for L, n in zip(lens, ns):
-        got = [meta.split_range(L, span, s) for s in range(n)]
+    seg, pieces, mx, units = meta.decode_plan(lens, 4, slots=64)       # 16 segments over 4354 tokens
+    assert seg == 288 and seg % 32 == 0 and 16 * seg >= sum(lens) > 15 * seg - 32 * 16
+    assert pieces == [1, 1, 1, 16] and mx == 16 and units == 16 * 4
+    for b, (L, n) in enumerate(zip(lens, pieces)):
+        got = [meta.piece_range(lens, seg, b, i) for i in range(n)]
         assert got[0][0] == 0 and got[-1][1] == L
-        assert all(a[1] == b[0] for a, b in zip(got, got[1:])) and all(e > b for b, e in got)
-    # span doubles until the unit count fits the target
+        assert all(x[1] == y[0] for x, y in zip(got, got[1:])) and all(e > s for s, e in got)
+        assert all(e - s <= seg for s, e in got)
+    # brute force: mark the segment of every tape position, count distinct segments per request
+    owner = [i // seg for i in range(sum(lens))]
+    start = 0
+    for L, n in zip(lens, pieces):
+        assert len(set(owner[start:start + L])) == n
+        start += L
+    # never more segments than wavefront slots per head, never fewer than one, at least a tile each
     lens = workloads.draw_lengths(2, 0, 64, 512, 4096)
-    span, ns, mx, units = meta.decode_plan(lens, 32)
-    assert units <= meta.PLAN_TARGET_UNITS
-    half = sum((int(L) + span // 2 - 1) // (span // 2) for L in lens) * 32
-    assert span == 128 or half > meta.PLAN_TARGET_UNITS
+    seg, pieces, mx, units = meta.decode_plan(lens, 32)
+    assert units // 32 <= meta.PLAN_WAVE_SLOTS // 32 and (units // 32) * seg >= lens.sum() > (units // 32 - 1) * seg
+    assert meta.decode_plan([5], 8) == (32, [1], 1, 8)
+    assert meta.decode_plan([40], 8)[0:2] == (32, [2])
+    assert meta.decode_plan([7, 9], 4096)[0] == 32            # more heads than slots: one segment per head
