@@ -14,10 +14,17 @@
 //   O^T[d, row]   += V_tile^T[D x 64 keys] * P^T[64 keys x rows]         (A = V^T from LDS, B = P in registers)
 // Keys run along the rows of S^T, so a softmax reduction over keys is 16 in-lane values plus one
 // cross-lane exchange, and the result registers of the first product are, value for value, the B operand
-// of the second once V^T is stored in LDS with its keys permuted into the order the lanes hold them.
-// V is transposed once per tile by the whole workgroup on its way into LDS (registers, v_perm), not per
-// wavefront.  The running maximum is only refreshed when a tile exceeds it by more than 2^8, which keeps
-// the accumulator rescale off the common path; the final division by the running sum makes the result
+// of the second.
+//
+// Data movement: K and V tiles go from global memory straight into LDS (global_load_lds, 16 B per lane, no
+// registers), double buffered, one workgroup barrier per tile.  Both tiles keep their natural [key][d]
+// layout; the 16-byte chunks of a row are XOR-swizzled with the row number (applied to the global address,
+// since the LDS side of such a load is fixed) so that the MFMA operand reads are bank-conflict free.  The
+// V^T operand is read with the transposing LDS read (ds_read_b64_tr_b16): 16 lanes fetch a 4-key x 16-d
+// block and each lane receives the 4 keys of its own d.
+//
+// The running maximum is only refreshed when a tile exceeds it by more than 2^8, which keeps the
+// accumulator rescale off the common path; the final division by the running sum makes the result
 // independent of which reference maximum was used.
 #include <hip/hip_runtime.h>
 
@@ -33,10 +40,11 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int kBN = 64;          // keys per tile
-constexpr int kRows = 256;       // query rows per workgroup (4 wavefronts x 64)
-constexpr float kTau = 8.0f;     // lazy-rescale threshold in log2 units
+constexpr int kBN = 64;       // keys per tile
+constexpr int kRows = 256;    // query rows per workgroup (4 wavefronts x 64)
+constexpr float kTau = 8.0f;  // lazy-rescale threshold in log2 units
 
 template <int DT>
 struct PElem;
@@ -90,20 +98,29 @@ struct PrefillParams {
   float scale_log2e;
 };
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_base + 16*l.
+__device__ __forceinline__ void load_to_lds(const char* g, char* lds_base) {
+  __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)lds_base, 16, 0, 0);
+}
+
 template <int DT, int D>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int CH = D / 8;            // 16-byte chunks per head row
   constexpr int KS = D / 16;           // k-steps of the score product
   constexpr int DB = D / 32;           // 32-row d blocks of the value product
-  constexpr int RSK = D * 2 + 16;      // LDS row stride of the K tile [key][d]
-  constexpr int RSV = kBN * 2 + 16;    // LDS row stride of the V^T tile [d][key slot]
-  constexpr int KPASS = kBN * CH / 256;  // 16-byte K pieces per thread and tile
-  constexpr int VITEMS = (kBN / 4) * CH; // (4 keys x 8 d) blocks of a V tile
-  constexpr int VPASS = (VITEMS + 255) / 256;
-  __shared__ __attribute__((aligned(16))) char lds_k[kBN * RSK];
-  __shared__ __attribute__((aligned(16))) char lds_v[D * RSV];
+  constexpr int ROWB = D * 2;          // bytes per head row
+  constexpr int RPL = 256 / ROWB;      // rows per 256-byte LDS bank line
+  constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
+  constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
+  constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
+  __shared__ __attribute__((aligned(1024))) char lds_k[2][TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_v[2][TILEB];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, hi = lane >> 5;
   const int G = (int)p.group, tb = (int)p.tb;
 
@@ -123,11 +140,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const int total_keys = P + tok0 + ntok;      // keys the last token of the tile sees
   const int nkt = (total_keys + kBN - 1) / kBN;
   const uint32_t row_bytes = p.hkv * D * 2;
-  const char* kc = p.k_ptrs[b] + (size_t)g * D * 2;
-  const char* vc = p.v_ptrs[b] + (size_t)g * D * 2;
+  const char* kc = p.k_ptrs[b] + (size_t)g * ROWB;
+  const char* vc = p.v_ptrs[b] + (size_t)g * ROWB;
   const bool split_src = p.k_new != nullptr;
-  const char* kn = split_src ? p.k_new + (size_t)g * D * 2 : kc;
-  const char* vn = split_src ? p.v_new + (size_t)g * D * 2 : vc;
+  const char* kn = split_src ? p.k_new + (size_t)g * ROWB : kc;
+  const char* vn = split_src ? p.v_new + (size_t)g * ROWB : vc;
   const int new_row0 = split_src ? cu_b - P : 0;   // key j >= P lives at row j + new_row0 of kn / vn
 
   // Query rows of this lane (one per 32-column block) and their causal limits.
@@ -142,7 +159,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     q_valid[cb] = t < ntok;
     q_tok[cb] = min(t, ntok - 1);
     lim[cb] = P + tok0 + q_tok[cb];            // key j is visible iff j <= lim
-    const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * D * 2;
+    const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * ROWB;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
   }
@@ -156,63 +173,65 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       for (int i = 0; i < 16; ++i) acc[db][cb][i] = 0.f;
   float m_used[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 
-  // Staging registers: this thread's share of one K tile and one V tile.
-  u32x4 kst[KPASS], vst[VPASS][4];
+  // Tile loads.  Load i of this wavefront fills LDS rows (4*wave + i)*RPI .. +RPI-1; the lane lands in row
+  // ld_row + i*RPI (of the tile) at chunk position ld_pos and therefore fetches the chunk that the swizzle
+  // assigns to that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).
+  const int ld_row = wave * NLD * RPI + lane / CH, ld_pos = lane % CH;
+  int k_off[NLD], v_off[NLD];  // byte offset inside a head row of the chunk this lane fetches, per load
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int row = ld_row + i * RPI;
+    k_off[i] = (ld_pos ^ ((row / RPL) % CH)) * 16;
+    v_off[i] = (ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16;
+  }
   const int last_key = total_keys - 1;
-  auto key_ptr = [&](const char* cache, const char* fresh, int j) -> const char* {
-    j = min(j, last_key);
-    return j < P ? cache + (size_t)j * row_bytes : fresh + (size_t)(j + new_row0) * row_bytes;
-  };
-  auto load_tile = [&](int kt) {
+  auto issue_tile = [&](int kt, int buf) {
     const int j0 = kt * kBN;
+    char* lk = lds_k[buf] + wave * NLD * 1024;
+    char* lv = lds_v[buf] + wave * NLD * 1024;
+    if (j0 + kBN <= P) {
+      // whole tile inside the cached prefix: uniform base, fixed lane offsets
+      const char* kt0 = kc + (size_t)j0 * row_bytes;
+      const char* vt0 = vc + (size_t)j0 * row_bytes;
 #pragma unroll
-    for (int i = 0; i < KPASS; ++i) {
-      const int it = tid + i * 256;
-      kst[i] = *(const u32x4*)(key_ptr(kc, kn, j0 + it / CH) + (it % CH) * 16);
-    }
-#pragma unroll
-    for (int i = 0; i < VPASS; ++i) {
-      const int it = tid + i * 256;
-      if (VITEMS % 256 == 0 || it < VITEMS) {
-        const int kg = it / CH, c = it % CH;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) vst[i][kk] = *(const u32x4*)(key_ptr(vc, vn, j0 + 4 * kg + kk) + c * 16);
+      for (int i = 0; i < NLD; ++i) {
+        const uint32_t ro = (uint32_t)(ld_row + i * RPI) * row_bytes;
+        load_to_lds(kt0 + ro + k_off[i], lk + i * 1024);
+        load_to_lds(vt0 + ro + v_off[i], lv + i * 1024);
       }
-    }
-  };
-  auto store_tile = [&]() {
+    } else {
 #pragma unroll
-    for (int i = 0; i < KPASS; ++i) {
-      const int it = tid + i * 256;
-      *(u32x4*)(lds_k + (it / CH) * RSK + (it % CH) * 16) = kst[i];
-    }
-#pragma unroll
-    for (int i = 0; i < VPASS; ++i) {
-      const int it = tid + i * 256;
-      if (VITEMS % 256 == 0 || it < VITEMS) {
-        const int kg = it / CH, c = it % CH;
-        // keys 4kg..4kg+3 of the tile: block kg/8 of 32 keys; inside it key = 16*s + 8*x + 4*h + y sits at
-        // slot 16*s + 8*h + 4*x + y, the order in which a lane of the score product holds its keys.
-        const int k8 = kg & 7;
-        const int pos = 32 * (kg >> 3) + 16 * (k8 >> 2) + 8 * (k8 & 1) + 4 * ((k8 >> 1) & 1);
-#pragma unroll
-        for (int dd = 0; dd < 8; ++dd) {
-          const unsigned sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-          u32x2 w;
-          w[0] = __builtin_amdgcn_perm(vst[i][1][dd >> 1], vst[i][0][dd >> 1], sel);
-          w[1] = __builtin_amdgcn_perm(vst[i][3][dd >> 1], vst[i][2][dd >> 1], sel);
-          *(u32x2*)(lds_v + (8 * c + dd) * RSV + pos * 2) = w;
-        }
+      for (int i = 0; i < NLD; ++i) {
+        const int j = min(j0 + ld_row + i * RPI, last_key);
+        const bool cached = j < P;
+        const size_t ro = (size_t)(cached ? j : j + new_row0) * row_bytes;
+        load_to_lds((cached ? kc : kn) + ro + k_off[i], lk + i * 1024);
+        load_to_lds((cached ? vc : vn) + ro + v_off[i], lv + i * 1024);
       }
     }
   };
 
-  load_tile(0);
+  // Operand read offsets of this lane (bytes inside a tile), without the per-step part.
+  //  K operand (kb, ks): row 32*kb + col, chunk 2*ks + hi.
+  //  V^T operand (db, kb, s2, h4): transposing read; inside its 16-lane group lane i supplies the address of
+  //  key 32*kb + 16*s2 + 8*h4 + 4*hi + i/4, d = 32*db + 16*(col/16) + 4*(i%4), and receives the 4 keys
+  //  (in order) of d = 32*db + col.
+  const int kswz = ((col / RPL) % CH);              // K swizzle of row 32*kb + col (32 is a multiple of CH*RPL)
+  const int kbank = (col % RPL) * ROWB + 0;         // (kept for clarity: row offset is added below)
+  (void)kbank;
+  const int vi = col & 15, vgi = col >> 4;
+  const int v_key_lane = 4 * hi + (vi >> 2);        // + 32*kb + 16*s2 + 8*h4
+  const int v_chunk_lane = 2 * vgi + ((vi & 3) >> 1);  // + 4*db
+  const int v_within = 8 * (vi & 1);
+
+  issue_tile(0, 0);
   for (int kt = 0; kt < nkt; ++kt) {
-    __syncthreads();
-    store_tile();
-    __syncthreads();
-    if (kt + 1 < nkt) load_tile(kt + 1);
+    const int buf = kt & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of tile kt has landed
+    __syncthreads();                     // everyone's part has landed; buffer buf^1 is free again
+    if (kt + 1 < nkt) issue_tile(kt + 1, buf ^ 1);
+    const char* tk = lds_k[buf];
+    const char* tv = lds_v[buf];
     const int j0 = kt * kBN;
     const bool need_mask = j0 + kBN - 1 > P + tok0;   // some (row, key) pair of this tile may be hidden
 
@@ -225,7 +244,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 kf = *(const u32x4*)(lds_k + (32 * kb + col) * RSK + (16 * ks + 8 * hi) * 2);
+        const u32x4 kf = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
         s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
         s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
       }
@@ -267,7 +286,20 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const u32x4 vf = *(const u32x4*)(lds_v + (32 * db + col) * RSV + (32 * kb + 16 * s2 + 8 * hi) * 2);
+          s16x4 h[2];
+#pragma unroll
+          for (int h4 = 0; h4 < 2; ++h4) {
+            const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
+            const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
+            const char* a = tv + key * ROWB + chunk * 16 + v_within;
+            h[h4] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a);
+          }
+          u32x4 vf;
+          const u32x2 lo = __builtin_bit_cast(u32x2, h[0]), hi2 = __builtin_bit_cast(u32x2, h[1]);
+          vf[0] = lo[0];
+          vf[1] = lo[1];
+          vf[2] = hi2[0];
+          vf[3] = hi2[1];
           acc[db][0] = PElem<DT>::mfma(vf, pf[0][s2], acc[db][0]);
           acc[db][1] = PElem<DT>::mfma(vf, pf[1][s2], acc[db][1]);
         }
@@ -280,7 +312,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
     if (!q_valid[cb]) continue;
     const float inv = 1.0f / l_tot;
-    char* op = p.out + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * D * 2;
+    char* op = p.out + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * ROWB;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
