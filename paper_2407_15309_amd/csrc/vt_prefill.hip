@@ -29,6 +29,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <type_traits>
 
 #include "vt_internal.h"
 
@@ -224,85 +225,108 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const int v_chunk_lane = 2 * vgi + ((vi & 3) >> 1);  // + 4*db
   const int v_within = 8 * (vi & 1);
 
+  // One 32-key block of the current tile: scores, softmax weights, value product.
+  const float c = p.scale_log2e;
+  auto block = [&](auto mask_tag, const char* tk, const char* tv, int j0, int kb) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    f32x16 s[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const u32x4 kf = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
+      s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
+      s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
+    }
+    float tmax[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      if constexpr (MASK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
+          s[cb][i] = j <= lim[cb] ? s[cb][i] : -INFINITY;
+        }
+      }
+      float t = fmaxf(s[cb][0], s[cb][1]);
+#pragma unroll
+      for (int i = 2; i < 16; i += 2) t = fmaxf(t, fmaxf(s[cb][i], s[cb][i + 1]));
+      tmax[cb] = fmaxf(t, __shfl_xor(t, 32)) * c;
+    }
+    const bool grow0 = tmax[0] > m_used[0] + kTau, grow1 = tmax[1] > m_used[1] + kTau;
+    if (__builtin_amdgcn_ballot_w64(grow0 || grow1) != 0) {
+      // Rare: move the reference maxima and rescale the running sums and the accumulators.  The accumulators
+      // live in accumulation registers for the whole kernel (the MFMAs read and write them there); this is the
+      // only other code that touches them, so it goes through explicit moves.
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const float m_new = (cb ? grow1 : grow0) ? tmax[cb] : m_used[cb];
+        const float alpha = __builtin_amdgcn_exp2f(m_used[cb] - m_new);
+        m_used[cb] = m_new;
+        l_run[cb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float t;
+            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                         : "+a"(acc[db][cb][i]), "=&v"(t)
+                         : "v"(alpha));
+          }
+      }
+    }
+    u32x4 pf[2][2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      float pr[16], psum = 0.f;
+      const float nm = -m_used[cb];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][i], c, nm));
+        psum += pr[i];
+      }
+      l_run[cb] += psum;
+      pf[cb][0] = PElem<DT>::pack8(pr);
+      pf[cb][1] = PElem<DT>::pack8(pr + 8);
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        s16x4 h[2];
+#pragma unroll
+        for (int h4 = 0; h4 < 2; ++h4) {
+          const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
+          const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
+          const char* a = tv + key * ROWB + chunk * 16 + v_within;
+          h[h4] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a);
+        }
+        u32x4 vf;
+        const u32x2 lo = __builtin_bit_cast(u32x2, h[0]), hi2 = __builtin_bit_cast(u32x2, h[1]);
+        vf[0] = lo[0];
+        vf[1] = lo[1];
+        vf[2] = hi2[0];
+        vf[3] = hi2[1];
+        acc[db][0] = PElem<DT>::mfma(vf, pf[0][s2], acc[db][0]);
+        acc[db][1] = PElem<DT>::mfma(vf, pf[1][s2], acc[db][1]);
+      }
+  };
+
   issue_tile(0, 0);
   for (int kt = 0; kt < nkt; ++kt) {
     const int buf = kt & 1;
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of tile kt has landed
     __syncthreads();                     // everyone's part has landed; buffer buf^1 is free again
     if (kt + 1 < nkt) issue_tile(kt + 1, buf ^ 1);
-    const char* tk = lds_k[buf];
-    const char* tv = lds_v[buf];
     const int j0 = kt * kBN;
-    const bool need_mask = j0 + kBN - 1 > P + tok0;   // some (row, key) pair of this tile may be hidden
-
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16 s[2];
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 kf = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
-        s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
-        s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
-      }
-      u32x4 pf[2][2];
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        float x[16];
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          x[i] = s[cb][i] * p.scale_log2e;
-          if (need_mask) {
-            const int j = j0 + 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
-            x[i] = j <= lim[cb] ? x[i] : -INFINITY;
-          }
-          tmax = fmaxf(tmax, x[i]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const bool grow = tmax > m_used[cb] + kTau;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-          const float m_new = grow ? tmax : m_used[cb];
-          const float alpha = __builtin_amdgcn_exp2f(m_used[cb] - m_new);
-          m_used[cb] = m_new;
-          l_run[cb] *= alpha;
-#pragma unroll
-          for (int db = 0; db < DB; ++db) acc[db][cb] *= alpha;
-        }
-        float pr[16], psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          pr[i] = __builtin_amdgcn_exp2f(x[i] - m_used[cb]);
-          psum += pr[i];
-        }
-        l_run[cb] += psum;
-        pf[cb][0] = PElem<DT>::pack8(pr);
-        pf[cb][1] = PElem<DT>::pack8(pr + 8);
-      }
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          s16x4 h[2];
-#pragma unroll
-          for (int h4 = 0; h4 < 2; ++h4) {
-            const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
-            const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
-            const char* a = tv + key * ROWB + chunk * 16 + v_within;
-            h[h4] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a);
-          }
-          u32x4 vf;
-          const u32x2 lo = __builtin_bit_cast(u32x2, h[0]), hi2 = __builtin_bit_cast(u32x2, h[1]);
-          vf[0] = lo[0];
-          vf[1] = lo[1];
-          vf[2] = hi2[0];
-          vf[3] = hi2[1];
-          acc[db][0] = PElem<DT>::mfma(vf, pf[0][s2], acc[db][0]);
-          acc[db][1] = PElem<DT>::mfma(vf, pf[1][s2], acc[db][1]);
-        }
+    if (j0 + kBN - 1 > P + tok0) {       // some (row, key) pair of this tile may be hidden
+      block(std::true_type{}, lds_k[buf], lds_v[buf], j0, 0);
+      block(std::true_type{}, lds_k[buf], lds_v[buf], j0, 1);
+    } else {
+      block(std::false_type{}, lds_k[buf], lds_v[buf], j0, 0);
+      block(std::false_type{}, lds_k[buf], lds_v[buf], j0, 1);
     }
   }
 
