@@ -117,8 +117,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
   constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
-  __shared__ __attribute__((aligned(1024))) char lds_k[2][TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_v[2][TILEB];
+  // Four separate arrays (not one indexed by the buffer number) so that the compiler can tell that the
+  // in-flight global-to-LDS loads of the next tile do not alias the operand reads of the current one.
+  __shared__ __attribute__((aligned(1024))) char lds_k0[TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_k1[TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_v0[TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_v1[TILEB];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -166,13 +170,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   }
 
   f32x16 acc[DB][2];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[db][cb][i] = 0.f;
-  float m_used[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_used[2], l_run[2];
 
   // Tile loads.  Load i of this wavefront fills LDS rows (4*wave + i)*RPI .. +RPI-1; the lane lands in row
   // ld_row + i*RPI (of the tile) at chunk position ld_pos and therefore fetches the chunk that the swizzle
@@ -186,10 +184,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     v_off[i] = (ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16;
   }
   const int last_key = total_keys - 1;
-  auto issue_tile = [&](int kt, int buf) {
+  auto issue_tile = [&](int kt, char* tile_k, char* tile_v) {
     const int j0 = kt * kBN;
-    char* lk = lds_k[buf] + wave * NLD * 1024;
-    char* lv = lds_v[buf] + wave * NLD * 1024;
+    char* lk = tile_k + wave * NLD * 1024;
+    char* lv = tile_v + wave * NLD * 1024;
     if (j0 + kBN <= P) {
       // whole tile inside the cached prefix: uniform base, fixed lane offsets
       const char* kt0 = kc + (size_t)j0 * row_bytes;
@@ -212,24 +210,20 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
 
-  // Operand read offsets of this lane (bytes inside a tile), without the per-step part.
+  // Operand reads of this lane.
   //  K operand (kb, ks): row 32*kb + col, chunk 2*ks + hi.
   //  V^T operand (db, kb, s2, h4): transposing read; inside its 16-lane group lane i supplies the address of
   //  key 32*kb + 16*s2 + 8*h4 + 4*hi + i/4, d = 32*db + 16*(col/16) + 4*(i%4), and receives the 4 keys
   //  (in order) of d = 32*db + col.
-  const int kswz = ((col / RPL) % CH);              // K swizzle of row 32*kb + col (32 is a multiple of CH*RPL)
-  const int kbank = (col % RPL) * ROWB + 0;         // (kept for clarity: row offset is added below)
-  (void)kbank;
+  const int kswz = ((col / RPL) % CH);  // K swizzle of row 32*kb + col (32 is a multiple of CH*RPL)
   const int vi = col & 15, vgi = col >> 4;
-  const int v_key_lane = 4 * hi + (vi >> 2);        // + 32*kb + 16*s2 + 8*h4
+  const int v_key_lane = 4 * hi + (vi >> 2);           // + 32*kb + 16*s2 + 8*h4
   const int v_chunk_lane = 2 * vgi + ((vi & 3) >> 1);  // + 4*db
   const int v_within = 8 * (vi & 1);
-
-  // One 32-key block of the current tile: scores, softmax weights, value product.
   const float c = p.scale_log2e;
-  auto block = [&](auto mask_tag, const char* tk, const char* tv, int j0, int kb) {
-    constexpr bool MASK = decltype(mask_tag)::value;
-    f32x16 s[2];
+
+  // S^T block = K[32 keys of block kb] Q^T: 2*KS MFMAs.
+  auto scores = [&](const char* tk, int kb, f32x16* s) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -240,44 +234,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
       s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
     }
-    float tmax[2];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      if constexpr (MASK) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int j = j0 + 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
-          s[cb][i] = j <= lim[cb] ? s[cb][i] : -INFINITY;
-        }
-      }
-      float t = fmaxf(s[cb][0], s[cb][1]);
-#pragma unroll
-      for (int i = 2; i < 16; i += 2) t = fmaxf(t, fmaxf(s[cb][i], s[cb][i + 1]));
-      tmax[cb] = fmaxf(t, __shfl_xor(t, 32)) * c;
-    }
-    const bool grow0 = tmax[0] > m_used[0] + kTau, grow1 = tmax[1] > m_used[1] + kTau;
-    if (__builtin_amdgcn_ballot_w64(grow0 || grow1) != 0) {
-      // Rare: move the reference maxima and rescale the running sums and the accumulators.  The accumulators
-      // live in accumulation registers for the whole kernel (the MFMAs read and write them there); this is the
-      // only other code that touches them, so it goes through explicit moves.
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const float m_new = (cb ? grow1 : grow0) ? tmax[cb] : m_used[cb];
-        const float alpha = __builtin_amdgcn_exp2f(m_used[cb] - m_new);
-        m_used[cb] = m_new;
-        l_run[cb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float t;
-            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
-                         : "+a"(acc[db][cb][i]), "=&v"(t)
-                         : "v"(alpha));
-          }
-      }
-    }
-    u32x4 pf[2][2];
+  };
+  // Softmax weights of a score block against the current reference maxima; adds them to the running sums.
+  auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
       float pr[16], psum = 0.f;
@@ -291,6 +250,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       pf[cb][0] = PElem<DT>::pack8(pr);
       pf[cb][1] = PElem<DT>::pack8(pr + 8);
     }
+  };
+  // O^T += V^T[block kb] P^T: 4*DB MFMAs.
+  auto values = [&](const char* tv, int kb, u32x4 (*pf)[2]) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -313,21 +275,143 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         acc[db][1] = PElem<DT>::mfma(vf, pf[1][s2], acc[db][1]);
       }
   };
-
-  issue_tile(0, 0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of tile kt has landed
-    __syncthreads();                     // everyone's part has landed; buffer buf^1 is free again
-    if (kt + 1 < nkt) issue_tile(kt + 1, buf ^ 1);
-    const int j0 = kt * kBN;
-    if (j0 + kBN - 1 > P + tok0) {       // some (row, key) pair of this tile may be hidden
-      block(std::true_type{}, lds_k[buf], lds_v[buf], j0, 0);
-      block(std::true_type{}, lds_k[buf], lds_v[buf], j0, 1);
-    } else {
-      block(std::false_type{}, lds_k[buf], lds_v[buf], j0, 0);
-      block(std::false_type{}, lds_k[buf], lds_v[buf], j0, 1);
+  // Column maxima of a score block (over the lane's 16 keys and its partner half), in exp2 units.
+  auto block_max = [&](const f32x16* s, float* tmax) {
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      float t = fmaxf(s[cb][0], s[cb][1]);
+#pragma unroll
+      for (int i = 2; i < 16; i += 2) t = fmaxf(t, fmaxf(s[cb][i], s[cb][i + 1]));
+      tmax[cb] = fmaxf(t, __shfl_xor(t, 32)) * c;
     }
+  };
+
+  // Fast tile: every (row, key) pair visible, reference maxima fixed.  Straight-line code: the scores of the
+  // second half are issued before the weights of the first half are computed, and the value product of the
+  // first half before the weights of the second, so that matrix and vector work overlap.
+  auto fast_tile = [&](const char* tk, const char* tv) {
+    f32x16 s0[2], s1[2];
+    u32x4 p0[2][2], p1[2][2];
+    scores(tk, 0, s0);
+    scores(tk, 1, s1);
+    weights(s0, p0);
+    values(tv, 0, p0);
+    weights(s1, p1);
+    values(tv, 1, p1);
+  };
+
+  // Generic tile: causal mask, classic online softmax (reference maxima follow the data, accumulators
+  // rescaled when a maximum moves by more than kTau).
+  auto generic_tile = [&](const char* tk, const char* tv, int j0) {
+#pragma unroll 1
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s[2];
+      scores(tk, kb, s);
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = j0 + 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
+          s[cb][i] = j <= lim[cb] ? s[cb][i] : -INFINITY;
+        }
+      float tmax[2];
+      block_max(s, tmax);
+      const bool grow0 = tmax[0] > m_used[0] + kTau, grow1 = tmax[1] > m_used[1] + kTau;
+      if (__builtin_amdgcn_ballot_w64(grow0 || grow1) != 0) {
+        // The accumulators live in accumulation registers (the MFMAs read and write them there); this is the
+        // only other code that touches them, so it goes through explicit moves.
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const float m_new = (cb ? grow1 : grow0) ? tmax[cb] : m_used[cb];
+          const float alpha = __builtin_amdgcn_exp2f(m_used[cb] - m_new);
+          m_used[cb] = m_new;
+          l_run[cb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              float t;
+              asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                           : "+a"(acc[db][cb][i]), "=&v"(t)
+                           : "v"(alpha));
+            }
+        }
+      }
+      u32x4 pf[2][2];
+      weights(s, pf);
+      values(tv, kb, pf);
+    }
+  };
+
+  auto tile_ready = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the awaited tile has landed
+    __syncthreads();                     // everyone's part has landed, and the other buffer is free again
+  };
+
+  // Tiles whose last key every row of the workgroup may see: kt*64 + 63 <= P + tok0.
+  int nfast = min(nkt, (P + tok0 + 1) / kBN);
+  for (int attempt = 0;; ++attempt) {
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[db][cb][i] = 0.f;
+    m_used[0] = m_used[1] = -INFINITY;
+    l_run[0] = l_run[1] = 0.f;
+
+    issue_tile(0, lds_k0, lds_v0);
+    tile_ready();
+    if (nkt > 1) issue_tile(1, lds_k1, lds_v1);
+    int kt = 0;
+    if (nfast > 0) {
+      // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
+      // weights are fp16).  Rows whose later scores outgrow the representable range are caught below.
+      f32x16 s[2];
+      float tmax[2];
+      scores(lds_k0, 0, s);
+      block_max(s, tmax);
+      m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
+      m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
+      // After a tile: make the next one ready, then start loading the one after it into the buffer just read.
+      for (;;) {
+        fast_tile(lds_k0, lds_v0);
+        ++kt;
+        if (kt < nkt) {
+          tile_ready();
+          if (kt + 1 < nkt) issue_tile(kt + 1, lds_k0, lds_v0);
+        }
+        if (kt >= nfast) break;
+        fast_tile(lds_k1, lds_v1);
+        ++kt;
+        if (kt < nkt) {
+          tile_ready();
+          if (kt + 1 < nkt) issue_tile(kt + 1, lds_k1, lds_v1);
+        }
+        if (kt >= nfast) break;
+      }
+    }
+    while (kt < nkt) {
+      const bool odd = kt & 1;
+      generic_tile(odd ? lds_k1 : lds_k0, odd ? lds_v1 : lds_v0, kt * kBN);
+      ++kt;
+      if (kt < nkt) {
+        tile_ready();
+        if (kt + 1 < nkt) issue_tile(kt + 1, odd ? lds_k1 : lds_k0, odd ? lds_v1 : lds_v0);
+      }
+    }
+    if (attempt > 0 || nfast == 0) break;
+    // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones:
+    // then some sum or accumulator is no longer finite and the whole workgroup redoes its rows the classic way.
+    float chk = l_run[0] + l_run[1];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) chk += __builtin_fabsf(acc[db][cb][i]);
+    if (!__syncthreads_or(!(chk < INFINITY))) break;
+    nfast = 0;
   }
 
   // out[row, d] = acc / l.  acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row.
