@@ -200,7 +200,7 @@ typedef struct {
 /* Prefix-prefill attention: new token i of request b (absolute position P_b + i) attends keys
  * 0 .. P_b + i of concat(cached prefix, new tokens): the whole prefix plus the new tokens causally.
  * FlashAttention-style tiling on MFMA with fp32 accumulation.  Paper: Section 2.2.2 (prefix cache),
- * Section 6.2.2 (prefix-prefilling kernel).  Errors as vt_attn_decode; head_dim must be 128 or 64. */
+ * Section 6.2.2 (prefix-prefilling kernel).  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024, scale > 0. */
 int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* stream);
 
 /* Pre-sizes the context's workspace so that later attention calls never allocate. */

@@ -67,6 +67,7 @@ struct vt_ctx {
   vt_stats_t st;
   void* ws;
   uint64_t ws_bytes;
+  void* counters;  // 256 zeroed device bytes: work counters of the persistent prefill kernel
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;
@@ -80,6 +81,7 @@ namespace vt {
 inline bool ok_ctx(const vt_ctx* c) { return c && c->magic == VT_CTX_MAGIC; }
 inline bool ok_kv(const vt_kv* k) { return k && k->magic == VT_KV_MAGIC && k->alive && ok_ctx(k->ctx); }
 
+constexpr int kMaxPrefillBatch = 1024;  // requests per prefix-prefill launch (the item order lives in LDS)
 constexpr int kMaxDecodeBatch = 4096;  // requests per decode launch (the tape prefix table lives in LDS)
 
 // Integer plan of a decode call (see vt_plan in vt.h).

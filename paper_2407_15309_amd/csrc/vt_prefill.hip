@@ -97,6 +97,7 @@ struct PrefillParams {
   const int32_t* plens;
   uint32_t batch, hq, hkv, group, tb;  // tb = new tokens per workgroup = 256 / group
   float scale_log2e;
+  unsigned* counters;                  // [0] next work item, [1] workgroups that have left; zero between launches
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -123,22 +124,64 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_k1[TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_v0[TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_v1[TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_k2[TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_v2[TILEB];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, hi = lane >> 5;
   const int G = (int)p.group, tb = (int)p.tb;
 
-  // Which (request, token tile) is this workgroup?  grid.x enumerates the tiles of all requests in order.
-  int rem = blockIdx.x, b = 0, N = 0;
-  for (;; ++b) {
-    if (b >= (int)p.batch) return;
+  // Work items are (request, token tile, kv head).  The workgroups are persistent and take items from a device
+  // counter, longest first: requests in descending order of prefix + new length, within a request the later
+  // (longer) token tiles first, kv heads innermost.
+  __shared__ int s_ord[kMaxPrefillBatch];      // s_ord[rank] = request
+  __shared__ int s_pre[kMaxPrefillBatch + 1];  // items of the requests ranked before
+  __shared__ int s_item;
+  {
+    const int B = (int)p.batch;
+    for (int r = tid; r < B; r += 256) {
+      const int key = p.plens[r] + p.cu[r + 1] - p.cu[r];
+      int rank = 0;
+      for (int u = 0; u < B; ++u) {
+        const int ku = p.plens[u] + p.cu[u + 1] - p.cu[u];
+        rank += (ku > key || (ku == key && u < r)) ? 1 : 0;
+      }
+      s_ord[rank] = r;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int n_before = 0;
+      for (int rank = 0; rank < B; ++rank) {
+        s_pre[rank] = n_before;
+        const int r = s_ord[rank];
+        n_before += ((p.cu[r + 1] - p.cu[r] + tb - 1) / tb) * (int)p.hkv;
+      }
+      s_pre[B] = n_before;
+      s_item = (int)atomicAdd(&p.counters[0], 1u);
+    }
+    __syncthreads();
+  }
+  const int n_items = s_pre[p.batch];
+  int item = s_item;
+  __syncthreads();
+  for (; item < n_items;) {
+  int next_item = 0;
+  if (tid == 0) next_item = (int)atomicAdd(&p.counters[0], 1u);  // in flight while this item is processed
+  int b, rem, g, N;
+  {
+    int lo = 0, hi_r = (int)p.batch;  // last rank with s_pre[rank] <= item
+    while (hi_r - lo > 1) {
+      const int mid = (lo + hi_r) >> 1;
+      if (s_pre[mid] <= item) lo = mid; else hi_r = mid;
+    }
+    b = s_ord[lo];
+    const int local = item - s_pre[lo];
     N = p.cu[b + 1] - p.cu[b];
     const int nt = (N + tb - 1) / tb;
-    if (rem < nt) break;
-    rem -= nt;
+    g = local % (int)p.hkv;
+    rem = nt - 1 - local / (int)p.hkv;
   }
-  const int g = blockIdx.y;
   const int cu_b = p.cu[b], P = p.plens[b];
   const int tok0 = rem * tb;
   const int ntok = min(tb, N - tok0);
@@ -343,9 +386,19 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
 
-  auto tile_ready = [&]() {
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the awaited tile has landed
-    __syncthreads();                     // everyone's part has landed, and the other buffer is free again
+  // Three tile buffers: while tile kt is computed, tiles kt+1 and kt+2 are in flight.  Called after tile kt-1
+  // has been computed (kt already advanced): waits until this wavefront's part of tile kt has landed - the
+  // younger loads of tile kt+1 may stay outstanding, the loads complete in order - then, past the barrier,
+  // everyone's part has landed and the buffer of tile kt-1 is free and takes tile kt+2.
+  constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
+  auto advance = [&](int kt, char* free_k, char* free_v) {
+    if (kt >= nkt) return;
+    if (kt + 1 < nkt)
+      __builtin_amdgcn_s_waitcnt(0x0f70 | VM);  // vmcnt(VM)
+    else
+      __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0)
+    __syncthreads();
+    if (kt + 2 < nkt) issue_tile(kt + 2, free_k, free_v);
   };
 
   // Tiles whose last key every row of the workgroup may see: kt*64 + 63 <= P + tok0.
@@ -361,8 +414,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     l_run[0] = l_run[1] = 0.f;
 
     issue_tile(0, lds_k0, lds_v0);
-    tile_ready();
-    if (nkt > 1) issue_tile(1, lds_k1, lds_v1);
+    if (nkt > 1) {
+      issue_tile(1, lds_k1, lds_v1);
+      __builtin_amdgcn_s_waitcnt(0x0f70 | VM);
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+    }
+    __syncthreads();
+    if (nkt > 2) issue_tile(2, lds_k2, lds_v2);
     int kt = 0;
     if (nfast > 0) {
       // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
@@ -373,32 +432,24 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       block_max(s, tmax);
       m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
       m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
-      // After a tile: make the next one ready, then start loading the one after it into the buffer just read.
       for (;;) {
         fast_tile(lds_k0, lds_v0);
-        ++kt;
-        if (kt < nkt) {
-          tile_ready();
-          if (kt + 1 < nkt) issue_tile(kt + 1, lds_k0, lds_v0);
-        }
+        advance(++kt, lds_k0, lds_v0);
         if (kt >= nfast) break;
         fast_tile(lds_k1, lds_v1);
-        ++kt;
-        if (kt < nkt) {
-          tile_ready();
-          if (kt + 1 < nkt) issue_tile(kt + 1, lds_k1, lds_v1);
-        }
+        advance(++kt, lds_k1, lds_v1);
+        if (kt >= nfast) break;
+        fast_tile(lds_k2, lds_v2);
+        advance(++kt, lds_k2, lds_v2);
         if (kt >= nfast) break;
       }
     }
     while (kt < nkt) {
-      const bool odd = kt & 1;
-      generic_tile(odd ? lds_k1 : lds_k0, odd ? lds_v1 : lds_v0, kt * kBN);
-      ++kt;
-      if (kt < nkt) {
-        tile_ready();
-        if (kt + 1 < nkt) issue_tile(kt + 1, odd ? lds_k1 : lds_k0, odd ? lds_v1 : lds_v0);
-      }
+      const int m3 = kt % 3;
+      char* ck = m3 == 0 ? lds_k0 : (m3 == 1 ? lds_k1 : lds_k2);
+      char* cv = m3 == 0 ? lds_v0 : (m3 == 1 ? lds_v1 : lds_v2);
+      generic_tile(ck, cv, kt * kBN);
+      advance(++kt, ck, cv);
     }
     if (attempt > 0 || nfast == 0) break;
     // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones:
@@ -431,6 +482,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         *(u32x2*)(op + (32 * db + 8 * q4 + 4 * hi) * 2) = w;
       }
   }
+  // next item (the barriers also keep the LDS tiles of this item safe from the next item's loads)
+  __syncthreads();
+  if (tid == 0) s_item = next_item;
+  __syncthreads();
+  item = s_item;
+  }  // item loop
+
+  // Leave the counters at zero for the next launch: the last workgroup out resets them.
+  if (tid == 0) {
+    const unsigned old = atomicAdd(&p.counters[1], 1u);
+    if (old == gridDim.x - 1) {
+      p.counters[0] = 0u;
+      p.counters[1] = 0u;
+    }
+  }
 }
 
 }  // namespace
@@ -459,9 +525,11 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
     tiles += (n + p.tb - 1) / p.tb;
   }
   if (tiles == 0) return VT_OK;
-  if (tiles > 0x7fffffffull || a->n_kv_heads > 65535) return VT_E_UNSUPPORTED;
+  const uint64_t items = tiles * a->n_kv_heads;
+  if (items > 0x7fffffffull || a->batch > (uint32_t)kMaxPrefillBatch || !ctx->counters) return VT_E_UNSUPPORTED;
+  p.counters = (unsigned*)ctx->counters;
   hipStream_t st = (hipStream_t)stream;
-  dim3 grid((uint32_t)tiles, a->n_kv_heads);
+  dim3 grid((uint32_t)(items < (uint64_t)ctx->n_cus ? items : (uint64_t)ctx->n_cus));
   prof_begin(ctx, 1, st);
   if (a->dtype == VT_BF16 && a->head_dim == 128)
     hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128>), grid, dim3(256), 0, st, p);
