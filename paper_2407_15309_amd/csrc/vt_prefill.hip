@@ -211,6 +211,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
   }
+  // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
+  // the vector registers to the scores, the weights and the in-flight LDS operand reads.
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
 
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
@@ -218,37 +224,37 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // Tile loads.  Load i of this wavefront fills LDS rows (4*wave + i)*RPI .. +RPI-1; the lane lands in row
   // ld_row + i*RPI (of the tile) at chunk position ld_pos and therefore fetches the chunk that the swizzle
   // assigns to that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).
-  const int ld_row = wave * NLD * RPI + lane / CH, ld_pos = lane % CH;
-  int k_off[NLD], v_off[NLD];  // byte offset inside a head row of the chunk this lane fetches, per load
-#pragma unroll
-  for (int i = 0; i < NLD; ++i) {
-    const int row = ld_row + i * RPI;
-    k_off[i] = (ld_pos ^ ((row / RPL) % CH)) * 16;
-    v_off[i] = (ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16;
-  }
   const int last_key = total_keys - 1;
   auto issue_tile = [&](int kt, char* tile_k, char* tile_v) {
+    // The lane's row and chunk offsets are recomputed from the lane number on every call (the asm hides the
+    // value from loop-invariant hoisting): keeping them live across the compute phases costs vector registers
+    // the hot loop needs, and a spill there would put scratch loads - and their waits - between these loads.
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    const int ld_row = wave * NLD * RPI + l / CH, ld_pos = l % CH;
     const int j0 = kt * kBN;
     char* lk = tile_k + wave * NLD * 1024;
     char* lv = tile_v + wave * NLD * 1024;
     if (j0 + kBN <= P) {
-      // whole tile inside the cached prefix: uniform base, fixed lane offsets
+      // whole tile inside the cached prefix: uniform base, 32-bit lane offsets
       const char* kt0 = kc + (size_t)j0 * row_bytes;
       const char* vt0 = vc + (size_t)j0 * row_bytes;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const uint32_t ro = (uint32_t)(ld_row + i * RPI) * row_bytes;
-        load_to_lds(kt0 + ro + k_off[i], lk + i * 1024);
-        load_to_lds(vt0 + ro + v_off[i], lv + i * 1024);
+        const int row = ld_row + i * RPI;
+        const uint32_t ro = (uint32_t)row * row_bytes;
+        load_to_lds(kt0 + (ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16)), lk + i * 1024);
+        load_to_lds(vt0 + (ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16)), lv + i * 1024);
       }
     } else {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int j = min(j0 + ld_row + i * RPI, last_key);
+        const int row = ld_row + i * RPI;
+        const int j = min(j0 + row, last_key);
         const bool cached = j < P;
         const size_t ro = (size_t)(cached ? j : j + new_row0) * row_bytes;
-        load_to_lds((cached ? kc : kn) + ro + k_off[i], lk + i * 1024);
-        load_to_lds((cached ? vc : vn) + ro + v_off[i], lv + i * 1024);
+        load_to_lds((cached ? kc : kn) + ro + (ld_pos ^ ((row / RPL) % CH)) * 16, lk + i * 1024);
+        load_to_lds((cached ? vc : vn) + ro + (ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16, lv + i * 1024);
       }
     }
   };
@@ -265,18 +271,27 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const int v_within = 8 * (vi & 1);
   const float c = p.scale_log2e;
 
-  // S^T block = K[32 keys of block kb] Q^T: 2*KS MFMAs.
-  auto scores = [&](const char* tk, int kb, f32x16* s) {
+  // K operands of the 32-key block kb (one per k-step), and S^T block = K Q^T: 2*KS MFMAs.
+  auto load_k = [&](const char* tk, int kb, u32x4* kf) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      kf[ks] = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
+  };
+  auto mma_scores = [&](const u32x4* kf, f32x16* s) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const u32x4 kf = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
-      s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
-      s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
+      s[0] = PElem<DT>::mfma(kf[ks], qf[0][ks], s[0]);
+      s[1] = PElem<DT>::mfma(kf[ks], qf[1][ks], s[1]);
     }
+  };
+  auto scores = [&](const char* tk, int kb, f32x16* s) {
+    u32x4 kf[KS];
+    load_k(tk, kb, kf);
+    mma_scores(kf, s);
   };
   // Softmax weights of a score block against the current reference maxima; adds them to the running sums.
   auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
@@ -294,8 +309,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       pf[cb][1] = PElem<DT>::pack8(pr + 8);
     }
   };
-  // O^T += V^T[block kb] P^T: 4*DB MFMAs.
-  auto values = [&](const char* tv, int kb, u32x4 (*pf)[2]) {
+  // V^T operands of block kb (one per (d block, 16-key step)), and O^T += V^T P^T: 4*DB MFMAs.
+  auto load_v = [&](const char* tv, int kb, u32x4* vf) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -308,15 +323,28 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
           const char* a = tv + key * ROWB + chunk * 16 + v_within;
           h[h4] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a);
         }
-        u32x4 vf;
         const u32x2 lo = __builtin_bit_cast(u32x2, h[0]), hi2 = __builtin_bit_cast(u32x2, h[1]);
-        vf[0] = lo[0];
-        vf[1] = lo[1];
-        vf[2] = hi2[0];
-        vf[3] = hi2[1];
-        acc[db][0] = PElem<DT>::mfma(vf, pf[0][s2], acc[db][0]);
-        acc[db][1] = PElem<DT>::mfma(vf, pf[1][s2], acc[db][1]);
+        u32x4 f;
+        f[0] = lo[0];
+        f[1] = lo[1];
+        f[2] = hi2[0];
+        f[3] = hi2[1];
+        vf[2 * db + s2] = f;
       }
+  };
+  auto mma_values = [&](const u32x4* vf, u32x4 (*pf)[2]) {
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        acc[db][0] = PElem<DT>::mfma(vf[2 * db + s2], pf[0][s2], acc[db][0]);
+        acc[db][1] = PElem<DT>::mfma(vf[2 * db + s2], pf[1][s2], acc[db][1]);
+      }
+  };
+  auto values = [&](const char* tv, int kb, u32x4 (*pf)[2]) {
+    u32x4 vf[2 * DB];
+    load_v(tv, kb, vf);
+    mma_values(vf, pf);
   };
   // Column maxima of a score block (over the lane's 16 keys and its partner half), in exp2 units.
   auto block_max = [&](const f32x16* s, float* tmax) {
@@ -335,12 +363,23 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   auto fast_tile = [&](const char* tk, const char* tv) {
     f32x16 s0[2], s1[2];
     u32x4 p0[2][2], p1[2][2];
-    scores(tk, 0, s0);
-    scores(tk, 1, s1);
+    u32x4 k0[KS], k1[KS], v0[2 * DB], v1[2 * DB];
+    // operand reads run one stage ahead of the MFMAs that use them (a single wavefront per SIMD has nobody
+    // else to hide the LDS latency behind)
+    load_k(tk, 0, k0);
+    load_k(tk, 1, k1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_scores(k0, s0);
+    load_v(tv, 0, v0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_scores(k1, s1);
     weights(s0, p0);
-    values(tv, 0, p0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(tv, 1, v1);
+    mma_values(v0, p0);
     weights(s1, p1);
-    values(tv, 1, p1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_values(v1, p1);
   };
 
   // Generic tile: causal mask, classic online softmax (reference maxima follow the data, accumulators
