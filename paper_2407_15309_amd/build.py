@@ -18,7 +18,10 @@ LIB = os.path.join(HERE, "libvt.so")
 SOURCES = ["vt_mem.cpp", "vt_attn.cpp", "vt_decode.hip", "vt_prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-private-field"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-private-field",
+         # let each MFMA take its accumulator from vector or accumulation registers as the allocator sees fit
+         # (the prefill kernel keeps O and Q in accumulation registers and the short-lived scores in vector ones)
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def _compile(src: str) -> str:
