@@ -171,6 +171,7 @@ int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) 
   if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
   if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
   if (!supported_dim(a->head_dim)) return VT_E_UNSUPPORTED;
+  if (!(a->scale > 0.0f) || !(a->scale < 3.0e38f)) return VT_E_INVALID;  // the kernel orders scores before scaling
   if (a->cu_seqlens_host[0] != 0 || (uint32_t)a->cu_seqlens_host[a->batch] != a->total_new_tokens) return VT_E_INVALID;
   for (uint32_t b = 0; b < a->batch; ++b)
     if (a->cu_seqlens_host[b + 1] < a->cu_seqlens_host[b] || a->prefix_lens_host[b] < 0) return VT_E_INVALID;

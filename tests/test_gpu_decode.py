@@ -243,3 +243,39 @@ def test_steady_state_decode_steps_with_extend_and_append(ctx):
             sum(int(meta.chunks_for_len(int(L), 8, 128) > meta.chunks_for_len(int(L) - cfg.steps, 8, 128)) for L in lens))
     finally:
         reg.release()
+
+
+def test_config5_full_size_two_steps(ctx):
+    """Config 5 at full size (batch 256, 64/8 heads, lengths 1024..8192): two decode steps, each extending every
+    request by one token and appending its K/V row; every output is compared with the oracle and the region
+    metadata with its closed forms."""
+    cfg = CONFIGS[5]
+    data = workloads.decode_inputs(cfg, threads=16)
+    say("config5: sum(L)", int(data["kv_lens"].sum()), "bytes/step", meta.decode_kv_bytes(data["kv_lens"], 8, 128))
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=cfg.kv_len[1] + cfg.steps)
+    try:
+        lens = reg.lens.copy()
+        k = [oracle.widen(x, cfg.dtype) for x in data["k"]]
+        v = [oracle.widen(x, cfg.dtype) for x in data["v"]]
+        for step in range(2):
+            si = workloads.step_inputs(cfg, step)
+            lens = lens + 1
+            vt.vt_extend_batch(reg.kvs, lens.tolist())
+            lens_dev = torch.from_numpy(lens).cuda()
+            vt.vt_append_batch(ctx, reg.k_ptrs, reg.v_ptrs, lens_dev, dev_bits(si["k_row"]), dev_bits(si["v_row"]),
+                               cfg.batch, cfg.n_kv_heads, cfg.head_dim, stream())
+            got = run_decode(ctx, cfg.dtype, si["q"], reg.k_ptrs, reg.v_ptrs, lens, cfg.n_kv_heads, cfg.scale, lens_dev)
+            plan, pieces = vt.vt_plan_decode(ctx, lens, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim)
+            assert (plan.span_tokens, pieces.tolist(), plan.max_splits, plan.n_units) == meta.decode_plan(lens, 8)
+            for b in range(cfg.batch):
+                k[b] = np.concatenate([k[b], oracle.widen(si["k_row"][b], cfg.dtype)[None]])
+                v[b] = np.concatenate([v[b], oracle.widen(si["v_row"][b], cfg.dtype)[None]])
+            for b in (0, 17, 255):
+                info = vt.vt_query(reg.kvs[b])
+                assert info.len == lens[b] and info.chunks_mapped == meta.chunks_for_len(int(lens[b]), 8, 128)
+            ref = oracle.decode(oracle.widen(si["q"], cfg.dtype), k, v, cfg.scale)
+            err = float(np.abs(oracle.widen(got, cfg.dtype) - ref).max())
+            say("  step", step, "max abs err", err)
+            assert err <= TOL[cfg.dtype]
+    finally:
+        reg.release()

@@ -194,6 +194,29 @@ def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
         reg.release()
 
 
+@pytest.mark.parametrize("dtype,boost,where", [("bf16", 40.0, 250), ("f16", 6.0, 250), ("bf16", 40.0, 0),
+                                               ("f16", 6.0, 3), ("bf16", 40.0, 299)])
+def test_scores_far_above_the_first_keys(ctx, dtype, boost, where):
+    """One cached key whose score exceeds everything seen before it by hundreds of units: the kernel's fast
+    path works with reference maxima fixed after the first keys and must notice that its weights overflow
+    (key late in the prefix) or simply underflow the rest (key among the first ones); either way the result is
+    the oracle's, which is dominated by that key's value row."""
+    cfg, d = with_lens(CONFIGS[3].replace(dtype=dtype), [300, 200], [70, 130], seed=77)
+    one = np.array([1.0], np.float32)
+    bits = lambda x: workloads.gen._round_bits(np.full((cfg.n_kv_heads, cfg.head_dim), x, np.float32), dtype)
+    half = oracle.widen(bits(0.5), dtype)[0, 0]
+    assert half == 0.5
+    # queries get a +0.5 offset in every coordinate, key `where` of request 0 is boost in every coordinate
+    q = oracle.widen(d["q_new"], dtype) + 0.5
+    d["q_new"] = workloads.gen._round_bits(q.astype(np.float32), dtype)
+    d["k"][0][where] = bits(boost)
+    got = check_prefill(ctx, cfg, d, "dominant-key-%d" % where)
+    want = oracle.widen(d["v"][0][where], dtype)                      # [Hkv, D]
+    rows = oracle.widen(got[: 70], dtype)                             # request 0, all heads
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    assert np.abs(rows - np.repeat(want, G, axis=0)[None]).max() <= TOL[dtype]
+
+
 def test_bad_arguments_are_refused(ctx):
     t = torch.zeros(4, 8, 128, dtype=torch.int16).cuda()
     cu, pl = np.array([0, 4], np.int32), np.array([3], np.int32)
@@ -203,7 +226,8 @@ def test_bad_arguments_are_refused(ctx):
     for change, status in ((dict(v_new=None), vt.VT_E_INVALID), (dict(head_dim=80), vt.VT_E_UNSUPPORTED),
                            (dict(total_new_tokens=5), vt.VT_E_INVALID), (dict(n_kv_heads=5), vt.VT_E_INVALID),
                            (dict(prefix_lens_host=np.array([-1], np.int32)), vt.VT_E_INVALID),
-                           (dict(out=None), vt.VT_E_INVALID)):
+                           (dict(out=None), vt.VT_E_INVALID), (dict(scale=0.0), vt.VT_E_INVALID),
+                           (dict(scale=-1.0), vt.VT_E_INVALID)):
         with pytest.raises(vt.VtError) as e:
             vt.vt_attn_prefix_prefill(ctx, vt.make_prefill_args(**dict(ok, **change)), stream())
         assert e.value.status == status, change
