@@ -279,3 +279,50 @@ def test_config5_full_size_two_steps(ctx):
             assert err <= TOL[cfg.dtype]
     finally:
         reg.release()
+
+
+def test_prefix_sharing_maps_the_same_chunks_into_a_second_region(ctx):
+    """Prefix match by aliasing (paper Section 4.4): the second request's region starts with the SAME physical
+    chunks as the first one's - no copy, no new memory - then grows privately; decode over the shared prefix gives
+    identical bits through either region."""
+    cfg = CONFIGS[5].replace(batch=1, kv_len=(2048, 2048))      # 2 chunks of 1024 rows per region
+    data = workloads.decode_inputs(cfg, seed=91)
+    reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=4096)
+    dst = None
+    try:
+        phys = vt.vt_stats(ctx).phys_bytes
+        try:
+            dst = vt.vt_share_prefix(reg.kvs[0], 2048, 4096)
+        except vt.VtError as e:
+            if e.status == vt.VT_E_DRIVER:
+                pytest.skip("the driver refused to map a chunk at a second address")
+            raise
+        assert vt.vt_stats(ctx).phys_bytes == phys               # nothing allocated
+        info = vt.vt_query(dst)
+        assert info.len == 2048 and info.shared_chunks == 2 and info.k_ptr != vt.vt_query(reg.kvs[0]).k_ptr
+        lens = np.array([2048], np.int32)
+        a = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, lens, cfg.n_kv_heads, cfg.scale)
+        kp = torch.tensor([info.k_ptr], dtype=torch.int64).cuda()
+        vp = torch.tensor([info.v_ptr], dtype=torch.int64).cuda()
+        b = run_decode(ctx, cfg.dtype, data["q"], kp, vp, lens, cfg.n_kv_heads, cfg.scale)
+        np.testing.assert_array_equal(a, b)
+        # the sharer grows on private chunks and decodes over prefix + its own rows
+        extra = workloads.normal_bits(92, 3, 0, (100, 8, 128), cfg.dtype)
+        extra_v = workloads.normal_bits(92, 4, 0, (100, 8, 128), cfg.dtype)
+        vt.vt_extend(dst, 2148)
+        vt.vt_append(dst, dev_bits(extra), dev_bits(extra_v), 100, 2048, stream())
+        assert vt.vt_stats(ctx).phys_bytes == phys + 2 * (2 << 20)
+        lens2 = np.array([2148], np.int32)
+        got = run_decode(ctx, cfg.dtype, data["q"], kp, vp, lens2, cfg.n_kv_heads, cfg.scale)
+        w = lambda x: oracle.widen(x, cfg.dtype)
+        ref = oracle.decode(w(data["q"]), [np.concatenate([w(data["k"][0]), w(extra)])],
+                            [np.concatenate([w(data["v"][0]), w(extra_v)])], cfg.scale)
+        assert np.abs(w(got) - ref).max() <= TOL[cfg.dtype]
+        # the owner is untouched
+        c = run_decode(ctx, cfg.dtype, data["q"], reg.k_ptrs, reg.v_ptrs, lens, cfg.n_kv_heads, cfg.scale)
+        np.testing.assert_array_equal(a, c)
+    finally:
+        torch.cuda.synchronize()
+        if dst is not None:
+            vt.vt_release(dst)
+        reg.release()
