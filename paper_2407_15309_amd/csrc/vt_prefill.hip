@@ -66,6 +66,12 @@ struct PElem<VT_BF16> {
     bf16x2 v = {(__bf16)a, (__bf16)b};
     return __builtin_bit_cast(unsigned, v);
   }
+  // acc + both halves of a packed pair
+  static __device__ __forceinline__ float add_pair(unsigned w, float acc) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                           false);
+  }
 };
 template <>
 struct PElem<VT_F16> {
@@ -83,6 +89,10 @@ struct PElem<VT_F16> {
     typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
     f16x2 v = {(_Float16)a, (_Float16)b};
     return __builtin_bit_cast(unsigned, v);
+  }
+  static __device__ __forceinline__ float add_pair(unsigned w, float acc) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), __builtin_bit_cast(f16x2, 0x3c003c00u), acc, false);
   }
 };
 
@@ -103,9 +113,42 @@ struct PrefillParams {
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_base + 16*l.
-__device__ __forceinline__ void load_to_lds(const char* g, char* lds_base) {
-  __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)lds_base, 16, 0, 0);
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr uniform).
+// Written as assembly so that these loads are invisible to the compiler's wait-count bookkeeping: it would
+// otherwise guard operand reads of the tile buffers with waits for every outstanding load.  The kernel places
+// its own waits (wait_loads) and barriers.  Two address forms: uniform base + 32-bit lane offset, or a 64-bit
+// lane address.  (m0 is written here; nothing else in this file uses it.)
+__device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_off), "s"(base), "s"(lds_addr)
+               : "memory");
+}
+__device__ __forceinline__ void dma16(const char* lane_addr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(lane_addr), "s"(lds_addr)
+               : "memory");
+}
+// Marks a value that is the same in every lane as such (it then lives in scalar registers).
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const char* uni(const char* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
+  return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+// Compile-time loop: f(integral_constant<int, I0>), ..., f(integral_constant<int, I1 - 1>).
+template <int I0, int I1, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I0 < I1) {
+    f(std::integral_constant<int, I0>{});
+    static_for<I0 + 1, I1>(f);
+  }
 }
 
 template <int DT, int D>
@@ -118,14 +161,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
   constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
-  // Four separate arrays (not one indexed by the buffer number) so that the compiler can tell that the
-  // in-flight global-to-LDS loads of the next tile do not alias the operand reads of the current one.
-  __shared__ __attribute__((aligned(1024))) char lds_k0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_k1[TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_v0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_v1[TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_k2[TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_v2[TILEB];
+  // Four tile buffers (K tile, then V tile), separate arrays (not one array indexed by the buffer number) so
+  // that the compiler can tell that the in-flight global-to-LDS loads of later tiles do not alias the operand
+  // reads of the current one.  (Its bookkeeping of such loads distinguishes only a handful of arrays: with K
+  // and V in arrays of their own the eighth one fell back to waiting for every outstanding load.)
+  __shared__ __attribute__((aligned(1024))) char lds_t0[2 * TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_t1[2 * TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_t2[2 * TILEB];
+  __shared__ __attribute__((aligned(1024))) char lds_t3[2 * TILEB];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -162,12 +205,13 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
     __syncthreads();
   }
-  const int n_items = s_pre[p.batch];
-  int item = s_item;
+  // (values read from LDS are the same in every lane; readfirstlane tells the compiler so, which keeps the
+  // item's pointers and lengths in scalar registers)
+  const int n_items = __builtin_amdgcn_readfirstlane(s_pre[p.batch]);
+  int item = __builtin_amdgcn_readfirstlane(s_item);
   __syncthreads();
   for (; item < n_items;) {
   int next_item = 0;
-  if (tid == 0) next_item = (int)atomicAdd(&p.counters[0], 1u);  // in flight while this item is processed
   int b, rem, g, N;
   {
     int lo = 0, hi_r = (int)p.batch;  // last rank with s_pre[rank] <= item
@@ -175,21 +219,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       const int mid = (lo + hi_r) >> 1;
       if (s_pre[mid] <= item) lo = mid; else hi_r = mid;
     }
-    b = s_ord[lo];
-    const int local = item - s_pre[lo];
-    N = p.cu[b + 1] - p.cu[b];
+    lo = __builtin_amdgcn_readfirstlane(lo);
+    b = __builtin_amdgcn_readfirstlane(s_ord[lo]);
+    const int local = item - __builtin_amdgcn_readfirstlane(s_pre[lo]);
+    N = uni(p.cu[b + 1] - p.cu[b]);
     const int nt = (N + tb - 1) / tb;
     g = local % (int)p.hkv;
     rem = nt - 1 - local / (int)p.hkv;
   }
-  const int cu_b = p.cu[b], P = p.plens[b];
+  const int cu_b = uni(p.cu[b]), P = uni(p.plens[b]);
   const int tok0 = rem * tb;
   const int ntok = min(tb, N - tok0);
   const int total_keys = P + tok0 + ntok;      // keys the last token of the tile sees
   const int nkt = (total_keys + kBN - 1) / kBN;
   const uint32_t row_bytes = p.hkv * D * 2;
-  const char* kc = p.k_ptrs[b] + (size_t)g * ROWB;
-  const char* vc = p.v_ptrs[b] + (size_t)g * ROWB;
+  const char* kc = uni(p.k_ptrs[b]) + (size_t)g * ROWB;
+  const char* vc = uni(p.v_ptrs[b]) + (size_t)g * ROWB;
   const bool split_src = p.k_new != nullptr;
   const char* kn = split_src ? p.k_new + (size_t)g * ROWB : kc;
   const char* vn = split_src ? p.v_new + (size_t)g * ROWB : vc;
@@ -225,39 +270,37 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // ld_row + i*RPI (of the tile) at chunk position ld_pos and therefore fetches the chunk that the swizzle
   // assigns to that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).
   const int last_key = total_keys - 1;
-  auto issue_tile = [&](int kt, char* tile_k, char* tile_v) {
-    // The lane's row and chunk offsets are recomputed from the lane number on every call (the asm hides the
-    // value from loop-invariant hoisting): keeping them live across the compute phases costs vector registers
-    // the hot loop needs, and a spill there would put scratch loads - and their waits - between these loads.
-    int l = lane;
+  // issue_part<i>: loads number i (one of K, one of V) of tile kt.  Every row chooses between the region and
+  // the new rows, clamped to the last key.  The lane's row and chunk offsets are recomputed from the lane number
+  // on every call (the asm hides the value from loop-invariant hoisting): keeping them live across the compute
+  // phases costs vector registers the hot loop needs.  A tile's loads are issued a pair at a time between the
+  // compute stages rather than back to back: the memory pipeline takes a 1 KiB load every 16 cycles or so, and
+  // a wavefront that issues eight of them in a row (next to three other wavefronts doing the same) stalls.
+  auto issue_part = [&](auto part, int kt, char* tile_k, char* tile_v) {
+    constexpr int i = decltype(part)::value;
+    unsigned l = (unsigned)lane;
     asm volatile("" : "+v"(l));
-    const int ld_row = wave * NLD * RPI + l / CH, ld_pos = l % CH;
-    const int j0 = kt * kBN;
-    char* lk = tile_k + wave * NLD * 1024;
-    char* lv = tile_v + wave * NLD * 1024;
-    if (j0 + kBN <= P) {
-      // whole tile inside the cached prefix: uniform base, 32-bit lane offsets
-      const char* kt0 = kc + (size_t)j0 * row_bytes;
-      const char* vt0 = vc + (size_t)j0 * row_bytes;
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int row = ld_row + i * RPI;
-        const uint32_t ro = (uint32_t)row * row_bytes;
-        load_to_lds(kt0 + (ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16)), lk + i * 1024);
-        load_to_lds(vt0 + (ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16)), lv + i * 1024);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int row = ld_row + i * RPI;
-        const int j = min(j0 + row, last_key);
-        const bool cached = j < P;
-        const size_t ro = (size_t)(cached ? j : j + new_row0) * row_bytes;
-        load_to_lds((cached ? kc : kn) + ro + (ld_pos ^ ((row / RPL) % CH)) * 16, lk + i * 1024);
-        load_to_lds((cached ? vc : vn) + ro + (ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16, lv + i * 1024);
-      }
+    const int row = wave * NLD * RPI + i * RPI + (int)(l / CH), ld_pos = (int)(l % CH);
+    const uint32_t lk = (uint32_t)uni((int)lds_addr_of(tile_k) + (wave * NLD + i) * 1024);
+    const uint32_t lv = (uint32_t)uni((int)lds_addr_of(tile_v) + (wave * NLD + i) * 1024);
+    const int j = min(kt * kBN + row, last_key);
+    const bool cached = j < P;
+    const size_t ro = (size_t)(uint32_t)(cached ? j : j + new_row0) * row_bytes;
+    dma16((cached ? kc : kn) + (ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16)), lk);
+    dma16((cached ? vc : vn) + (ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16)), lv);
+  };
+  auto issue_rest = [&](int kt, char* tile_k, char* tile_v) {  // parts 1 .. NLD-1
+    issue_part(std::integral_constant<int, 1>{}, kt, tile_k, tile_v);
+    if constexpr (NLD > 2) {
+      issue_part(std::integral_constant<int, 2>{}, kt, tile_k, tile_v);
+      issue_part(std::integral_constant<int, 3>{}, kt, tile_k, tile_v);
     }
   };
+  auto issue_tile = [&](int kt, char* tile_k, char* tile_v) {
+    issue_part(std::integral_constant<int, 0>{}, kt, tile_k, tile_v);
+    issue_rest(kt, tile_k, tile_v);
+  };
+  static_assert(NLD == 2 || NLD == 4, "tile load split");
 
   // Operand reads of this lane.
   //  K operand (kb, ks): row 32*kb + col, chunk 2*ks + hi.
@@ -277,42 +320,48 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     for (int ks = 0; ks < KS; ++ks)
       kf[ks] = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
   };
+  auto mma_scores_cb = [&](const u32x4* kf, int cb, f32x16* s) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s[cb] = PElem<DT>::mfma(kf[ks], qf[cb][ks], s[cb]);
+  };
   auto mma_scores = [&](const u32x4* kf, f32x16* s) {
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      s[0] = PElem<DT>::mfma(kf[ks], qf[0][ks], s[0]);
-      s[1] = PElem<DT>::mfma(kf[ks], qf[1][ks], s[1]);
-    }
+    mma_scores_cb(kf, 0, s);
+    mma_scores_cb(kf, 1, s);
   };
   auto scores = [&](const char* tk, int kb, f32x16* s) {
     u32x4 kf[KS];
     load_k(tk, kb, kf);
     mma_scores(kf, s);
   };
-  // Softmax weights of a score block against the current reference maxima; adds them to the running sums.
-  auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
+  // Softmax weights of a score block against the current reference maxima, rounded to the storage type (they
+  // are the MFMA operand), and their sum added to the running sums.  The sum is taken over the rounded weights,
+  // two per instruction (dot product of a packed pair with ones): the normaliser then matches the numerator
+  // exactly, and the adds cost half as many instructions.
+  auto weights_cb = [&](const f32x16* s, int cb, u32x4 (*pf)[2]) {
+    float pr[16];
+    const float nm = -m_used[cb];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      float pr[16], psum = 0.f;
-      const float nm = -m_used[cb];
+    for (int i = 0; i < 16; ++i) pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][i], c, nm));
+    pf[cb][0] = PElem<DT>::pack8(pr);
+    pf[cb][1] = PElem<DT>::pack8(pr + 8);
+    float psum = 0.f, psum2 = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][i], c, nm));
-        psum += pr[i];
-      }
-      l_run[cb] += psum;
-      pf[cb][0] = PElem<DT>::pack8(pr);
-      pf[cb][1] = PElem<DT>::pack8(pr + 8);
+    for (int w = 0; w < 4; ++w) {
+      psum = PElem<DT>::add_pair(pf[cb][0][w], psum);
+      psum2 = PElem<DT>::add_pair(pf[cb][1][w], psum2);
     }
+    l_run[cb] += psum + psum2;
+  };
+  auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
+    weights_cb(s, 0, pf);
+    weights_cb(s, 1, pf);
   };
   // V^T operands of block kb (one per (d block, 16-key step)), and O^T += V^T P^T: 4*DB MFMAs.
-  auto load_v = [&](const char* tv, int kb, u32x4* vf) {
+  auto load_v_part = [&](const char* tv, int kb, u32x4* vf, int db0, int db1) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = db0; db < db1; ++db)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         s16x4 h[2];
@@ -332,6 +381,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         vf[2 * db + s2] = f;
       }
   };
+  auto load_v = [&](const char* tv, int kb, u32x4* vf) { load_v_part(tv, kb, vf, 0, DB); };
   auto mma_values = [&](const u32x4* vf, u32x4 (*pf)[2]) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -357,30 +407,176 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
 
-  // Fast tile: every (row, key) pair visible, reference maxima fixed.  Straight-line code: the scores of the
-  // second half are issued before the weights of the first half are computed, and the value product of the
-  // first half before the weights of the second, so that matrix and vector work overlap.
-  auto fast_tile = [&](const char* tk, const char* tv) {
+  // Waits until at most `n` of this wavefront's global-to-LDS loads are outstanding.
+  auto wait_loads = [](auto n) {
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+  };
+  constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
+  // Tile pipeline.  Tile t lives in buffer t % 4.  While tile kt is computed, tiles kt+1 and kt+2 are in flight
+  // or landed.  Every tile kt follows the same protocol.  Before its synchronisation point it issues loads
+  // 1 and 2 of tile kt+2 (only load 1 when a tile has two loads per tensor).  At the synchronisation point the
+  // wavefront waits until its own part of tile kt+1 has landed - loads complete in order, so it waits until at
+  // most the SYNC_N loads issued after that tile's last one are outstanding - then, past the barrier, everyone's
+  // part has landed and everyone is done with tile kt-1.  After it, it issues the last load of tile kt+2 (when
+  // there are four) and load 0 of tile kt+3, which goes into the buffer of tile kt-1.  Past the last tile the
+  // refills repeat tile nkt-1 (into buffers nobody reads), which keeps the count of outstanding loads, and with
+  // it the wait, the same on every tile.  The barrier is the bare instruction: the fence of __syncthreads
+  // would wait for all outstanding loads.
+  constexpr int SYNC_N = NLD > 2 ? VM - 2 : VM;
+  const std::integral_constant<int, 0> part0;
+  const std::integral_constant<int, 1> part1;
+  const std::integral_constant<int, 2> part2;
+  const std::integral_constant<int, 3> part3;
+  auto issue_before_sync = [&](int kt, char* gk, char* gv) {
+    const int t2 = min(kt + 2, nkt - 1);
+    issue_part(part1, t2, gk, gv);
+    if constexpr (NLD > 2) issue_part(part2, t2, gk, gv);
+  };
+  auto sync_next = [&]() {
+    wait_loads(std::integral_constant<int, SYNC_N>{});
+    __builtin_amdgcn_s_barrier();
+  };
+  auto issue_after_sync = [&](int kt, char* gk, char* gv, char* fk, char* fv) {
+    if constexpr (NLD > 2) issue_part(part3, min(kt + 2, nkt - 1), gk, gv);
+    issue_part(part0, min(kt + 3, nkt - 1), fk, fv);
+  };
+
+  // One of the nine steps that turn a 32-key x 32-row score block (16 values per lane) into weights: step
+  // j < 8 computes weights 2j and 2j+1, step j >= 1 packs the previous pair into word j-1 of the MFMA operand
+  // and adds the pair (as rounded) to the partial sum.
+  auto weight_step = [&](auto jc, const f32x16& sv, float nm, float* pr, u32x4* pw, float& ps) {
+    constexpr int j = decltype(jc)::value;
+    if constexpr (j < 8) {
+      pr[2 * j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], c, nm));
+      pr[2 * j + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], c, nm));
+    }
+    if constexpr (j >= 1) {
+      const unsigned w = PElem<DT>::pack2(pr[2 * j - 2], pr[2 * j - 1]);
+      pw[(j - 1) / 4][(j - 1) % 4] = w;
+      ps = PElem<DT>::add_pair(w, ps);
+    }
+  };
+  // One transposing read of a V^T operand half: read r of block kb covers d block r/4, 16-key step (r/2)%2,
+  // 8-key half r%2; operand 2*db + s2 is the pair of reads 2m, 2m+1.
+  auto read_v = [&](auto rc, const char* tv, int kb) -> u32x2 {
+    constexpr int r = decltype(rc)::value;
+    constexpr int db = r / 4, s2 = (r / 2) % 2, h4 = r % 2;
+    const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
+    const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
+    const char* a = tv + key * ROWB + chunk * 16 + v_within;
+    return __builtin_bit_cast(u32x2,
+                              __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a));
+  };
+  auto read_k = [&](auto ksc, const char* tk, int kb) -> u32x4 {
+    constexpr int ks = decltype(ksc)::value;
+    return *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
+  };
+  // MFMA i of the value product of one 32-key block: operand i/2, query column block i%2.
+  auto pv_mfma = [&](auto ic, const u32x2* vh, u32x4 (*pf)[2]) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int m = i / 2, cb = i % 2, db = m / 2, s2 = m % 2;
+    u32x4 f;
+    f[0] = vh[2 * m][0];
+    f[1] = vh[2 * m][1];
+    f[2] = vh[2 * m + 1][0];
+    f[3] = vh[2 * m + 1][1];
+    acc[db][cb] = PElem<DT>::mfma(f, pf[cb][s2], acc[db][cb]);
+  };
+
+  // Fast tile: every (row, key) pair visible, reference maxima fixed.  The instruction order is fixed by hand:
+  // the code is a sequence of slots, each one MFMA followed by a share of the vector, LDS and load-issue work
+  // that does not depend on it, and nothing moves between slots.  (Left to itself the scheduler puts long runs
+  // of exponentials between the MFMAs and leaves the matrix pipeline idle; a single wavefront per SIMD has
+  // nobody else to fill such gaps.)  Six stages; the scores are computed per 32-row half so that the weights
+  // of one half can be worked out beside the scores of the next:
+  //   A  S(block 0, rows 0-31)          | reads K block 1, issues loads of tile kt+2
+  //   B  S(block 0, rows 32-63)         | weights of A's scores, reads first half of V block 0
+  //   C  S(block 1, rows 0-31)          | weights of B's scores, reads second half of V block 0
+  //   D  S(block 1, rows 32-63)         | weights of C's scores
+  //   E  O += V(block 0) P(block 0)     | weights of D's scores, reads V block 1
+  //   -- synchronisation point --
+  //   F  O += V(block 1) P(block 1)     | issues loads of tiles kt+2 / kt+3, reads K block 0 of the next tile
+  // ck/cv: this tile; nk: K of the next tile; gk/gv: buffer of tile kt+2; fk/fv: buffer of tile kt+3.  k0 holds K
+  // block 0 of this tile on entry and of the next tile on exit.
+  constexpr int NPV = 4 * DB;  // MFMAs of one value product; also the transposing reads of one V block
+  static_assert(NPV == 2 * KS, "V reads are spread one per slot over two score stages");
+  auto fast_tile = [&](int kt, const char* ck, const char* cv, const char* nk, char* gk, char* gv, char* fk,
+                       char* fv, u32x4* k0) {
     f32x16 s0[2], s1[2];
     u32x4 p0[2][2], p1[2][2];
-    u32x4 k0[KS], k1[KS], v0[2 * DB], v1[2 * DB];
-    // operand reads run one stage ahead of the MFMAs that use them (a single wavefront per SIMD has nobody
-    // else to hide the LDS latency behind)
-    load_k(tk, 0, k0);
-    load_k(tk, 1, k1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_scores(k0, s0);
-    load_v(tv, 0, v0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_scores(k1, s1);
-    weights(s0, p0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(tv, 1, v1);
-    mma_values(v0, p0);
-    weights(s1, p1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_values(v1, p1);
+    u32x4 k1[KS];
+    u32x2 v0h[NPV], v1h[NPV];
+    float pr[16], ps;
+    const float nm0 = -m_used[0], nm1 = -m_used[1];
+    const int t2 = min(kt + 2, nkt - 1);
+    auto zero = [](f32x16& x) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = 0.f;
+    };
+    // A
+    zero(s0[0]);
+    static_for<0, KS>([&](auto i) {
+      s0[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0[0]);
+      k1[i] = read_k(i, ck, 1);
+      if constexpr (i == 0) issue_part(part1, t2, gk, gv);
+      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk, gv);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // B
+    zero(s0[1]);
+    ps = 0.f;
+    static_for<0, KS>([&](auto i) {
+      s0[1] = PElem<DT>::mfma(k0[i], qf[1][i], s0[1]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0[0], nm0, pr, p0[0], ps); });
+      v0h[i] = read_v(i, cv, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run[0] += ps;
+    // C
+    zero(s1[0]);
+    ps = 0.f;
+    static_for<0, KS>([&](auto i) {
+      s1[0] = PElem<DT>::mfma(k1[i], qf[0][i], s1[0]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0[1], nm1, pr, p0[1], ps); });
+      v0h[KS + i] = read_v(std::integral_constant<int, KS + i>{}, cv, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run[1] += ps;
+    // D
+    zero(s1[1]);
+    ps = 0.f;
+    static_for<0, KS>([&](auto i) {
+      s1[1] = PElem<DT>::mfma(k1[i], qf[1][i], s1[1]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s1[0], nm0, pr, p1[0], ps); });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run[0] += ps;
+    // E
+    ps = 0.f;
+    static_for<0, NPV>([&](auto i) {
+      pv_mfma(i, v0h, p0);
+      static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1[1], nm1, pr, p1[1], ps); });
+      v1h[i] = read_v(i, cv, 1);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run[1] += ps;
+    sync_next();
+    // F
+    static_for<0, NPV>([&](auto i) {
+      pv_mfma(i, v1h, p1);
+      if constexpr (i < KS) k0[i] = read_k(i, nk, 0);
+      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk, gv);
+      if constexpr (i == NPV / 2) issue_part(part0, min(kt + 3, nkt - 1), fk, fv);
+      __builtin_amdgcn_sched_barrier(0);
+    });
   };
+
+  auto buf_k = [&](int t) -> char* {
+    const int m = t & 3;
+    return m == 0 ? lds_t0 : (m == 1 ? lds_t1 : (m == 2 ? lds_t2 : lds_t3));
+  };
+  auto buf_v = [&](int t) -> char* { return buf_k(t) + TILEB; };
 
   // Generic tile: causal mask, classic online softmax (reference maxima follow the data, accumulators
   // rescaled when a maximum moves by more than kTau).
@@ -425,21 +621,6 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
 
-  // Three tile buffers: while tile kt is computed, tiles kt+1 and kt+2 are in flight.  Called after tile kt-1
-  // has been computed (kt already advanced): waits until this wavefront's part of tile kt has landed - the
-  // younger loads of tile kt+1 may stay outstanding, the loads complete in order - then, past the barrier,
-  // everyone's part has landed and the buffer of tile kt-1 is free and takes tile kt+2.
-  constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
-  auto advance = [&](int kt, char* free_k, char* free_v) {
-    if (kt >= nkt) return;
-    if (kt + 1 < nkt)
-      __builtin_amdgcn_s_waitcnt(0x0f70 | VM);  // vmcnt(VM)
-    else
-      __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0)
-    __syncthreads();
-    if (kt + 2 < nkt) issue_tile(kt + 2, free_k, free_v);
-  };
-
   // Tiles whose last key every row of the workgroup may see: kt*64 + 63 <= P + tok0.
   int nfast = min(nkt, (P + tok0 + 1) / kBN);
   for (int attempt = 0;; ++attempt) {
@@ -452,44 +633,44 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     m_used[0] = m_used[1] = -INFINITY;
     l_run[0] = l_run[1] = 0.f;
 
-    issue_tile(0, lds_k0, lds_v0);
-    if (nkt > 1) {
-      issue_tile(1, lds_k1, lds_v1);
-      __builtin_amdgcn_s_waitcnt(0x0f70 | VM);
-    } else {
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-    }
-    __syncthreads();
-    if (nkt > 2) issue_tile(2, lds_k2, lds_v2);
+    issue_tile(0, lds_t0, lds_t0 + TILEB);
+    issue_tile(min(1, nkt - 1), lds_t1, lds_t1 + TILEB);
+    issue_part(part0, min(2, nkt - 1), lds_t2, lds_t2 + TILEB);
+    wait_loads(std::integral_constant<int, VM + 2>{});
+    __builtin_amdgcn_s_barrier();
     int kt = 0;
     if (nfast > 0) {
       // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
       // weights are fp16).  Rows whose later scores outgrow the representable range are caught below.
-      f32x16 s[2];
-      float tmax[2];
-      scores(lds_k0, 0, s);
-      block_max(s, tmax);
-      m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
-      m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
+      u32x4 k0[KS];
+      load_k(lds_t0, 0, k0);
+      {
+        f32x16 s[2];
+        float tmax[2];
+        mma_scores(k0, s);
+        block_max(s, tmax);
+        m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
+        m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
+      }
       for (;;) {
-        fast_tile(lds_k0, lds_v0);
-        advance(++kt, lds_k0, lds_v0);
-        if (kt >= nfast) break;
-        fast_tile(lds_k1, lds_v1);
-        advance(++kt, lds_k1, lds_v1);
-        if (kt >= nfast) break;
-        fast_tile(lds_k2, lds_v2);
-        advance(++kt, lds_k2, lds_v2);
-        if (kt >= nfast) break;
+        fast_tile(kt, lds_t0, lds_t0 + TILEB, lds_t1, lds_t2, lds_t2 + TILEB, lds_t3, lds_t3 + TILEB, k0);
+        if (++kt >= nfast) break;
+        fast_tile(kt, lds_t1, lds_t1 + TILEB, lds_t2, lds_t3, lds_t3 + TILEB, lds_t0, lds_t0 + TILEB, k0);
+        if (++kt >= nfast) break;
+        fast_tile(kt, lds_t2, lds_t2 + TILEB, lds_t3, lds_t0, lds_t0 + TILEB, lds_t1, lds_t1 + TILEB, k0);
+        if (++kt >= nfast) break;
+        fast_tile(kt, lds_t3, lds_t3 + TILEB, lds_t0, lds_t1, lds_t1 + TILEB, lds_t2, lds_t2 + TILEB, k0);
+        if (++kt >= nfast) break;
       }
     }
-    while (kt < nkt) {
-      const int m3 = kt % 3;
-      char* ck = m3 == 0 ? lds_k0 : (m3 == 1 ? lds_k1 : lds_k2);
-      char* cv = m3 == 0 ? lds_v0 : (m3 == 1 ? lds_v1 : lds_v2);
-      generic_tile(ck, cv, kt * kBN);
-      advance(++kt, ck, cv);
+    for (; kt < nkt; ++kt) {
+      issue_before_sync(kt, buf_k(kt + 2), buf_v(kt + 2));
+      generic_tile(buf_k(kt), buf_v(kt), kt * kBN);
+      sync_next();
+      issue_after_sync(kt, buf_k(kt + 2), buf_v(kt + 2), buf_k(kt + 3), buf_v(kt + 3));
     }
+    // drain the repeated refills before anything else is loaded into the buffers
+    wait_loads(std::integral_constant<int, 0>{});
     if (attempt > 0 || nfast == 0) break;
     // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones:
     // then some sum or accumulator is no longer finite and the whole workgroup redoes its rows the classic way.
@@ -503,6 +684,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     if (!__syncthreads_or(!(chk < INFINITY))) break;
     nfast = 0;
   }
+
+  // The next item is claimed only now: a workgroup that claimed it at the start would sit on it for the whole
+  // current item while others idle at the end of the launch.  The atomic's latency hides behind the stores.
+  if (tid == 0) next_item = (int)atomicAdd(&p.counters[0], 1u);
 
   // out[row, d] = acc / l.  acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row.
 #pragma unroll
@@ -525,7 +710,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   __syncthreads();
   if (tid == 0) s_item = next_item;
   __syncthreads();
-  item = s_item;
+  item = __builtin_amdgcn_readfirstlane(s_item);
   }  // item loop
 
   // Leave the counters at zero for the next launch: the last workgroup out resets them.

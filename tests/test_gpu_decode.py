@@ -309,9 +309,13 @@ def test_prefix_sharing_maps_the_same_chunks_into_a_second_region(ctx):
         # the sharer grows on private chunks and decodes over prefix + its own rows
         extra = workloads.normal_bits(92, 3, 0, (100, 8, 128), cfg.dtype)
         extra_v = workloads.normal_bits(92, 4, 0, (100, 8, 128), cfg.dtype)
+        before = vt.vt_stats(ctx)
         vt.vt_extend(dst, 2148)
         vt.vt_append(dst, dev_bits(extra), dev_bits(extra_v), 100, 2048, stream())
-        assert vt.vt_stats(ctx).phys_bytes == phys + 2 * (2 << 20)
+        after = vt.vt_stats(ctx)
+        # one private chunk each for K and V, new or taken from the pool of released chunks
+        assert (after.chunks_created + after.chunks_reused) - (before.chunks_created + before.chunks_reused) == 2
+        assert after.mapped_bytes - before.mapped_bytes == 2 * (2 << 20)
         lens2 = np.array([2148], np.int32)
         got = run_decode(ctx, cfg.dtype, data["q"], kp, vp, lens2, cfg.n_kv_heads, cfg.scale)
         w = lambda x: oracle.widen(x, cfg.dtype)
