@@ -7,17 +7,25 @@
 // Section 4.1); the new tokens' rows come from k_new / v_new, or from the region itself when the caller
 // has already appended them.
 //
-// Tiling: a workgroup of 4 wavefronts owns 256 query rows of one (request, kv head): the G query heads of
-// the group for 256/G consecutive new tokens, so one K/V tile read serves every head of the group.  It
-// sweeps the visible keys in tiles of 64.  Per tile, with v_mfma_f32_32x32x16:
+// Tiling: a workgroup of 4 wavefronts computes 256 query rows of one (request, kv head) at a time: the G
+// query heads of the group for 256/G consecutive new tokens, so one K/V tile read serves every head of the
+// group.  It sweeps the visible keys in tiles of 64.  Per tile, with v_mfma_f32_32x32x16:
 //   S^T[key, row]  = K_tile[64 x D] * Q^T[D x 64 rows per wavefront]     (A = K from LDS, B = Q in registers)
 //   O^T[d, row]   += V_tile^T[D x 64 keys] * P^T[64 keys x rows]         (A = V^T from LDS, B = P in registers)
 // Keys run along the rows of S^T, so a softmax reduction over keys is 16 in-lane values plus one
 // cross-lane exchange, and the result registers of the first product are, value for value, the B operand
 // of the second.
 //
+// Work distribution: the (item, key tile) pairs of the whole call, items being (request, kv head, token
+// tile), form one sequence; workgroup w of n owns the w-th n-th of it.  A workgroup therefore computes some
+// whole items and at most two pieces of items it shares with its neighbours.  A whole item is normalised
+// and written out at once; a piece leaves its running maxima, sums and unnormalised accumulators in a
+// workspace slot, and a second kernel merges the pieces of every shared item.  Every workgroup gets the same
+// number of tiles whatever the mix of lengths, and a call with fewer items than compute units still fills
+// the chip.
+//
 // Data movement: K and V tiles go from global memory straight into LDS (global_load_lds, 16 B per lane, no
-// registers), double buffered, one workgroup barrier per tile.  Both tiles keep their natural [key][d]
+// registers), four tile buffers, one workgroup barrier per tile.  Both tiles keep their natural [key][d]
 // layout; the 16-byte chunks of a row are XOR-swizzled with the row number (applied to the global address,
 // since the LDS side of such a load is fixed) so that the MFMA operand reads are bank-conflict free.  The
 // V^T operand is read with the transposing LDS read (ds_read_b64_tr_b16): 16 lanes fetch a 4-key x 16-d
@@ -39,6 +47,7 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -46,6 +55,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 constexpr int kBN = 64;       // keys per tile
 constexpr int kRows = 256;    // query rows per workgroup (4 wavefronts x 64)
 constexpr float kTau = 8.0f;  // lazy-rescale threshold in log2 units
+constexpr int kMinCostPerGroup = 16;  // a workgroup gets at least the work of eight fast tiles
 
 template <int DT>
 struct PElem;
@@ -107,11 +117,60 @@ struct PrefillParams {
   const int32_t* plens;
   uint32_t batch, hq, hkv, group, tb;  // tb = new tokens per workgroup = 256 / group
   float scale_log2e;
-  unsigned* counters;                  // [0] next work item, [1] workgroups that have left; zero between launches
+  uint32_t total_cost, n_groups;       // cost units of the whole call, workgroups sharing them
+  float* ws;                           // 2 * n_groups piece slots, then n_groups shared-item records
 };
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+// Key tiles of item (request with P cached and N new tokens, token tile t of tb tokens).  The keys it sees
+// are the P cached rows and the first vis = min((t+1)*tb, N) new rows.  When the new rows come from a buffer
+// of their own (split), cached and new rows are tiled separately, so that no tile mixes the two sources.
+// A tile is fast when all its 64 keys exist and every query row of the token tile sees them; the others (the
+// ragged end of a segment, the causal diagonal) are masked and cost more.
+struct ItemShape {
+  int nkt, nfast;
+};
+__host__ __device__ inline ItemShape item_shape(int P, int N, int t, int tb, bool split) {
+  const int tok0 = t * tb;
+  const int vis = tok0 + tb < N ? tok0 + tb : N;
+  const int lenA = split ? P : P + vis, lenB = split ? vis : 0;
+  const int seenA = lenA < P + tok0 + 1 ? lenA : P + tok0 + 1;
+  ItemShape r;
+  r.nkt = (lenA + kBN - 1) / kBN + (lenB + kBN - 1) / kBN;
+  r.nfast = seenA / kBN + (split ? (tok0 + 1) / kBN : 0);
+  return r;
+}
+// The work of the call is measured in cost units: a fast tile is kFastCost units, a masked tile kMaskedCost
+// (their measured times are about 1.9 and 2.7 microseconds).  Units c .. of an item map to its tiles in sweep
+// order (fast tiles first); a tile belongs to whoever owns its first unit: tile_at(c) is the first tile whose
+// first unit is >= c.
+// An item starts with kItemCost units that belong to no tile: the fixed work of starting and finishing one
+// (about 8 microseconds).
+constexpr int kFastCost = 2, kMaskedCost = 3, kItemCost = 8;
+__host__ __device__ inline uint32_t item_cost(ItemShape s) {
+  return (uint32_t)(kItemCost + kFastCost * s.nfast + kMaskedCost * (s.nkt - s.nfast));
+}
+__host__ __device__ inline int tile_at(ItemShape s, uint32_t c) {
+  const int cc = (int)c > kItemCost ? (int)c - kItemCost : 0, cf = kFastCost * s.nfast;
+  return cc <= cf ? (cc + kFastCost - 1) / kFastCost : s.nfast + (cc - cf + kMaskedCost - 1) / kMaskedCost;
+}
+// Cost of all token tiles of one request, per kv head.
+__host__ __device__ inline uint32_t request_cost(int P, int N, int tb, bool split) {
+  uint32_t c = 0;
+  for (int t = 0; t * tb < N; ++t) c += item_cost(item_shape(P, N, t, tb, split));
+  return c;
+}
+// First cost unit of workgroup w.
+__host__ __device__ inline uint32_t group_begin(uint32_t total, uint32_t n, uint32_t w) {
+  return (uint32_t)((uint64_t)total * w / n);
+}
+// Floats of one piece slot: 256 maxima, 256 sums, 256 x D accumulators.
+__host__ __device__ constexpr uint32_t piece_floats(int d) { return 512u + 256u * (uint32_t)d; }
+// Record of an item that starts in a workgroup's range and ends in a later one (written by the main kernel,
+// read by the merge kernel).
+struct SharedItem {
+  uint32_t valid, cost_begin;  // first cost unit of the item in the whole sequence
+  int32_t b, g, t, nkt, nfast, pad;
+};
 
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr uniform).
 // Written as assembly so that these loads are invisible to the compiler's wait-count bookkeeping: it would
@@ -151,6 +210,60 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Where cost unit `cursor` of the whole sequence lies: item (b, g, t), unit c of it.  Items are ordered by
+// request, kv head, token tile.  s_pre[b] = cost of the requests before b (all heads).  Every value is the same
+// in all lanes.
+struct ItemPos {
+  int b, g, t;
+  uint32_t c;
+  ItemShape shape;
+};
+__device__ __forceinline__ int find_request(const PrefillParams& p, const uint32_t* s_pre, uint32_t cursor) {
+  int lo = 0, hi = (int)p.batch;  // last b with s_pre[b] <= cursor
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((uint32_t)uni((int)s_pre[mid]) <= cursor) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+// P and N of the request come from the caller (who may have them at hand).
+__device__ __forceinline__ ItemPos locate(const PrefillParams& p, const uint32_t* s_pre, uint32_t cursor, bool split,
+                                          int lo, int P, int N) {
+  ItemPos r;
+  r.b = lo;
+  const uint32_t first = (uint32_t)uni((int)s_pre[lo]);
+  const uint32_t per_head = ((uint32_t)uni((int)s_pre[lo + 1]) - first) / p.hkv;
+  const uint32_t local = cursor - first;
+  r.g = (int)(local / per_head);
+  uint32_t rem = local - (uint32_t)r.g * per_head;
+  int t = 0;
+  ItemShape sh = item_shape(P, N, 0, (int)p.tb, split);
+  while (rem >= item_cost(sh) && (t + 1) * (int)p.tb < N) {
+    rem -= item_cost(sh);
+    ++t;
+    sh = item_shape(P, N, t, (int)p.tb, split);
+  }
+  r.t = t;
+  r.c = rem;
+  r.shape = sh;
+  return r;
+}
+__device__ __forceinline__ void build_prefix(const PrefillParams& p, uint32_t* s_pre, int tid, bool split) {
+  const int B = (int)p.batch;
+  for (int r = tid; r < B; r += 256)
+    s_pre[r + 1] = request_cost(p.plens[r], p.cu[r + 1] - p.cu[r], (int)p.tb, split) * p.hkv;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t run = 0;
+    s_pre[0] = 0;
+    for (int r = 1; r <= B; ++r) {
+      run += s_pre[r];
+      s_pre[r] = run;
+    }
+  }
+  __syncthreads();
+}
+
 template <int DT, int D>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int CH = D / 8;            // 16-byte chunks per head row
@@ -161,146 +274,153 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
   constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
-  // Four tile buffers (K tile, then V tile), separate arrays (not one array indexed by the buffer number) so
-  // that the compiler can tell that the in-flight global-to-LDS loads of later tiles do not alias the operand
-  // reads of the current one.  (Its bookkeeping of such loads distinguishes only a handful of arrays: with K
-  // and V in arrays of their own the eighth one fell back to waiting for every outstanding load.)
+  // Four tile buffers (K tile, then V tile), separate arrays rather than one array indexed by the buffer number.
   __shared__ __attribute__((aligned(1024))) char lds_t0[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t1[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t2[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t3[2 * TILEB];
+  __shared__ uint32_t s_pre[kMaxPrefillBatch + 1];
+  // Lengths and region addresses of the first few requests this workgroup works on, fetched once: a piece then
+  // starts without a round trip to memory for them.
+  constexpr int kWin = 8;
+  __shared__ int s_wP[kWin], s_wN[kWin], s_wCu[kWin];
+  __shared__ const char* s_wK[kWin];
+  __shared__ const char* s_wV[kWin];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, hi = lane >> 5;
   const int G = (int)p.group, tb = (int)p.tb;
-
-  // Work items are (request, token tile, kv head).  The workgroups are persistent and take items from a device
-  // counter, longest first: requests in descending order of prefix + new length, within a request the later
-  // (longer) token tiles first, kv heads innermost.
-  __shared__ int s_ord[kMaxPrefillBatch];      // s_ord[rank] = request
-  __shared__ int s_pre[kMaxPrefillBatch + 1];  // items of the requests ranked before
-  __shared__ int s_item;
-  {
-    const int B = (int)p.batch;
-    for (int r = tid; r < B; r += 256) {
-      const int key = p.plens[r] + p.cu[r + 1] - p.cu[r];
-      int rank = 0;
-      for (int u = 0; u < B; ++u) {
-        const int ku = p.plens[u] + p.cu[u + 1] - p.cu[u];
-        rank += (ku > key || (ku == key && u < r)) ? 1 : 0;
-      }
-      s_ord[rank] = r;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int n_before = 0;
-      for (int rank = 0; rank < B; ++rank) {
-        s_pre[rank] = n_before;
-        const int r = s_ord[rank];
-        n_before += ((p.cu[r + 1] - p.cu[r] + tb - 1) / tb) * (int)p.hkv;
-      }
-      s_pre[B] = n_before;
-      s_item = (int)atomicAdd(&p.counters[0], 1u);
-    }
-    __syncthreads();
-  }
-  // (values read from LDS are the same in every lane; readfirstlane tells the compiler so, which keeps the
-  // item's pointers and lengths in scalar registers)
-  const int n_items = __builtin_amdgcn_readfirstlane(s_pre[p.batch]);
-  int item = __builtin_amdgcn_readfirstlane(s_item);
-  __syncthreads();
-  for (; item < n_items;) {
-  int next_item = 0;
-  int b, rem, g, N;
-  {
-    int lo = 0, hi_r = (int)p.batch;  // last rank with s_pre[rank] <= item
-    while (hi_r - lo > 1) {
-      const int mid = (lo + hi_r) >> 1;
-      if (s_pre[mid] <= item) lo = mid; else hi_r = mid;
-    }
-    lo = __builtin_amdgcn_readfirstlane(lo);
-    b = __builtin_amdgcn_readfirstlane(s_ord[lo]);
-    const int local = item - __builtin_amdgcn_readfirstlane(s_pre[lo]);
-    N = uni(p.cu[b + 1] - p.cu[b]);
-    const int nt = (N + tb - 1) / tb;
-    g = local % (int)p.hkv;
-    rem = nt - 1 - local / (int)p.hkv;
-  }
-  const int cu_b = uni(p.cu[b]), P = uni(p.plens[b]);
-  const int tok0 = rem * tb;
-  const int ntok = min(tb, N - tok0);
-  const int total_keys = P + tok0 + ntok;      // keys the last token of the tile sees
-  const int nkt = (total_keys + kBN - 1) / kBN;
-  const uint32_t row_bytes = p.hkv * D * 2;
-  const char* kc = uni(p.k_ptrs[b]) + (size_t)g * ROWB;
-  const char* vc = uni(p.v_ptrs[b]) + (size_t)g * ROWB;
   const bool split_src = p.k_new != nullptr;
-  const char* kn = split_src ? p.k_new + (size_t)g * ROWB : kc;
-  const char* vn = split_src ? p.v_new + (size_t)g * ROWB : vc;
-  const int new_row0 = split_src ? cu_b - P : 0;   // key j >= P lives at row j + new_row0 of kn / vn
+  const uint32_t row_bytes = p.hkv * D * 2;
+
+  build_prefix(p, s_pre, tid, split_src);
+  uint32_t cursor = group_begin(p.total_cost, p.n_groups, blockIdx.x);
+  const uint32_t range_end = group_begin(p.total_cost, p.n_groups, blockIdx.x + 1);
+  SharedItem* shared_items = (SharedItem*)(p.ws + (size_t)2 * p.n_groups * piece_floats(D));
+  SharedItem my_shared = {};
+  const int b_win = cursor < range_end ? find_request(p, s_pre, cursor) : 0;
+  if (tid < kWin && b_win + tid < (int)p.batch) {
+    const int r = b_win + tid;
+    s_wP[tid] = p.plens[r];
+    s_wCu[tid] = p.cu[r];
+    s_wN[tid] = p.cu[r + 1] - p.cu[r];
+    s_wK[tid] = p.k_ptrs[r];
+    s_wV[tid] = p.v_ptrs[r];
+  }
+  __syncthreads();
+
+  for (; cursor < range_end;) {
+  // ---- the piece: tiles s0 .. s1-1 of item (b, g, t): those whose first cost unit lies in this range ----
+  const int b = find_request(p, s_pre, cursor);
+  const bool in_win = b - b_win < kWin;
+  const int wi = in_win ? b - b_win : 0;
+  const int cu_b = uni(in_win ? s_wCu[wi] : p.cu[b]), P = uni(in_win ? s_wP[wi] : p.plens[b]);
+  const int N = uni(in_win ? s_wN[wi] : p.cu[b + 1] - p.cu[b]);
+  const ItemPos pos = locate(p, s_pre, cursor, split_src, b, P, N);
+  const uint32_t c1 = min(item_cost(pos.shape), pos.c + (range_end - cursor));
+  const int g = pos.g;
+  const int s0 = tile_at(pos.shape, pos.c), s1 = tile_at(pos.shape, c1);
+  const uint32_t piece_cursor = cursor;
+  cursor += c1 - pos.c;
+  if (s1 <= s0) continue;
+  const bool whole = s0 == 0 && s1 == pos.shape.nkt;
+  // A piece that continues an item goes to slot 2w, the first piece of an item that ends in a later range to slot
+  // 2w+1 (a workgroup has at most one of each).
+  const uint32_t slot = 2 * blockIdx.x + (s0 > 0 ? 0u : 1u);
+  if (!whole && s0 == 0) {
+    my_shared.valid = 1;
+    my_shared.cost_begin = piece_cursor - pos.c;
+    my_shared.b = b;
+    my_shared.g = g;
+    my_shared.t = pos.t;
+    my_shared.nkt = pos.shape.nkt;
+    my_shared.nfast = pos.shape.nfast;
+  }
+  const int tok0 = pos.t * tb;
+  const int ntok = min(tb, N - tok0);
+  const int vis = tok0 + ntok;                 // new rows the last token of the tile sees
+  // Two key segments: A = rows of the region (the cached prefix; also the new rows when they are already in the
+  // cache), B = rows of k_new / v_new.  Each is tiled from its own row 0.
+  const int lenA = split_src ? P : P + vis, lenB = split_src ? vis : 0;
+  const int nA = (lenA + kBN - 1) / kBN;
+  // Tiles whose 64 keys every row of the workgroup sees: inside a segment and not beyond the first token.
+  const int fastA = min(lenA, P + tok0 + 1) / kBN;
+  const int fastB = split_src ? (tok0 + 1) / kBN : 0;
+  const int nfast_item = fastA + fastB;
+  const char* kc = uni(in_win ? s_wK[wi] : p.k_ptrs[b]) + (size_t)g * ROWB;
+  const char* vc = uni(in_win ? s_wV[wi] : p.v_ptrs[b]) + (size_t)g * ROWB;
+  const char* kn = split_src ? uni(p.k_new + (size_t)cu_b * row_bytes + (size_t)g * ROWB) : kc;
+  const char* vn = split_src ? uni(p.v_new + (size_t)cu_b * row_bytes + (size_t)g * ROWB) : vc;
+  // The item's tiles are swept in this order: the fast tiles of A, the fast tiles of B, then the rest of A (its
+  // ragged last tile) and the rest of B (the causal diagonal).  Softmax does not care about the order of the
+  // keys, and this way the unmasked tiles come first.  Tile s of the sweep:
+  struct Tile {
+    const char* k;
+    const char* v;
+    int last_row;  // rows 0 .. last_row exist
+    int jbase;     // absolute position of the key in row 0
+  };
+  auto tile_of = [&](int s) -> Tile {
+    // (bitwise operators on purpose: plain scalar selects, no branches in the middle of the tile code)
+    const bool in_b = ((s >= fastA) & (s < nfast_item)) | (s >= nfast_item + nA - fastA);
+    const int tt = s - (s < fastA ? 0 : (s < nfast_item ? fastA : (in_b ? nA : fastB)));
+    Tile r;
+    const size_t off = (size_t)tt * kBN * row_bytes;
+    r.k = (in_b ? kn : kc) + off;
+    r.v = (in_b ? vn : vc) + off;
+    r.last_row = min(kBN, (in_b ? lenB : lenA) - tt * kBN) - 1;
+    r.jbase = (in_b ? P : 0) + tt * kBN;
+    return r;
+  };
 
   // Query rows of this lane (one per 32-column block) and their causal limits.
-  int lim[2], q_tok[2], q_head[2];
-  bool q_valid[2];
+  int lim[2];
   u32x4 qf[2][KS];
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
     const int r = wave * 64 + cb * 32 + col;
-    const int t = r / G;
-    q_head[cb] = r - t * G;
-    q_valid[cb] = t < ntok;
-    q_tok[cb] = min(t, ntok - 1);
-    lim[cb] = P + tok0 + q_tok[cb];            // key j is visible iff j <= lim
-    const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * ROWB;
+    const int t = r / G, q_head = r - t * G;
+    const int q_tok = min(t, ntok - 1);        // rows past the last token repeat it (and are not written)
+    lim[cb] = P + tok0 + q_tok;                // key j is visible iff j <= lim
+    const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok) * p.hq + (size_t)g * G + q_head) * ROWB;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
   }
-  // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
-  // the vector registers to the scores, the weights and the in-flight LDS operand reads.
-#pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
-
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
 
-  // Tile loads.  Load i of this wavefront fills LDS rows (4*wave + i)*RPI .. +RPI-1; the lane lands in row
-  // ld_row + i*RPI (of the tile) at chunk position ld_pos and therefore fetches the chunk that the swizzle
-  // assigns to that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).
-  const int last_key = total_keys - 1;
-  // issue_part<i>: loads number i (one of K, one of V) of tile kt.  Every row chooses between the region and
-  // the new rows, clamped to the last key.  The lane's row and chunk offsets are recomputed from the lane number
-  // on every call (the asm hides the value from loop-invariant hoisting): keeping them live across the compute
-  // phases costs vector registers the hot loop needs.  A tile's loads are issued a pair at a time between the
-  // compute stages rather than back to back: the memory pipeline takes a 1 KiB load every 16 cycles or so, and
-  // a wavefront that issues eight of them in a row (next to three other wavefronts doing the same) stalls.
-  auto issue_part = [&](auto part, int kt, char* tile_k, char* tile_v) {
+  // Tile loads.  Load i of this wavefront fills LDS rows (NLD*wave + i)*RPI .. +RPI-1 of the tile; the lane
+  // lands in row `row` at chunk position ld_pos and therefore fetches the chunk that the swizzle assigns to
+  // that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).  Rows past the
+  // end of the segment repeat its last row (they are masked later).  A tile's loads are issued a pair (one of
+  // K, one of V) at a time between the compute stages rather than back to back, and their lane offsets are
+  // recomputed from the lane number on every call (the asm hides the value from loop-invariant hoisting):
+  // keeping them live across the compute phases costs vector registers the hot loop needs.
+  auto issue_part = [&](auto part, const Tile& tl, char* tile_k, char* tile_v) {
     constexpr int i = decltype(part)::value;
     unsigned l = (unsigned)lane;
     asm volatile("" : "+v"(l));
     const int row = wave * NLD * RPI + i * RPI + (int)(l / CH), ld_pos = (int)(l % CH);
     const uint32_t lk = (uint32_t)uni((int)lds_addr_of(tile_k) + (wave * NLD + i) * 1024);
     const uint32_t lv = (uint32_t)uni((int)lds_addr_of(tile_v) + (wave * NLD + i) * 1024);
-    const int j = min(kt * kBN + row, last_key);
-    const bool cached = j < P;
-    const size_t ro = (size_t)(uint32_t)(cached ? j : j + new_row0) * row_bytes;
-    dma16((cached ? kc : kn) + (ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16)), lk);
-    dma16((cached ? vc : vn) + (ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16)), lv);
-  };
-  auto issue_rest = [&](int kt, char* tile_k, char* tile_v) {  // parts 1 .. NLD-1
-    issue_part(std::integral_constant<int, 1>{}, kt, tile_k, tile_v);
-    if constexpr (NLD > 2) {
-      issue_part(std::integral_constant<int, 2>{}, kt, tile_k, tile_v);
-      issue_part(std::integral_constant<int, 3>{}, kt, tile_k, tile_v);
-    }
-  };
-  auto issue_tile = [&](int kt, char* tile_k, char* tile_v) {
-    issue_part(std::integral_constant<int, 0>{}, kt, tile_k, tile_v);
-    issue_rest(kt, tile_k, tile_v);
+    const uint32_t ro = __umul24((unsigned)min(row, tl.last_row), row_bytes);
+    dma16(tl.k, ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16), lk);
+    dma16(tl.v, ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16), lv);
   };
   static_assert(NLD == 2 || NLD == 4, "tile load split");
+  const std::integral_constant<int, 0> part0;
+  const std::integral_constant<int, 1> part1;
+  const std::integral_constant<int, 2> part2;
+  const std::integral_constant<int, 3> part3;
+  auto issue_tile = [&](const Tile& tl, char* tile_k, char* tile_v) {
+    issue_part(part0, tl, tile_k, tile_v);
+    issue_part(part1, tl, tile_k, tile_v);
+    if constexpr (NLD > 2) {
+      issue_part(part2, tl, tile_k, tile_v);
+      issue_part(part3, tl, tile_k, tile_v);
+    }
+  };
 
   // Operand reads of this lane.
   //  K operand (kb, ks): row 32*kb + col, chunk 2*ks + hi.
@@ -314,87 +434,82 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const int v_within = 8 * (vi & 1);
   const float c = p.scale_log2e;
 
-  // K operands of the 32-key block kb (one per k-step), and S^T block = K Q^T: 2*KS MFMAs.
-  auto load_k = [&](const char* tk, int kb, u32x4* kf) {
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      kf[ks] = *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
+  auto read_k = [&](auto ksc, const char* tk, int kb) -> u32x4 {
+    constexpr int ks = decltype(ksc)::value;
+    return *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
   };
-  auto mma_scores_cb = [&](const u32x4* kf, int cb, f32x16* s) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[cb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s[cb] = PElem<DT>::mfma(kf[ks], qf[cb][ks], s[cb]);
+  // One transposing read of a V^T operand half: read r of block kb covers d block r/4, 16-key step (r/2)%2,
+  // 8-key half r%2; operand 2*db + s2 is the pair of reads 2m, 2m+1.
+  auto read_v = [&](auto rc, const char* tv, int kb) -> u32x2 {
+    constexpr int r = decltype(rc)::value;
+    constexpr int db = r / 4, s2 = (r / 2) % 2, h4 = r % 2;
+    const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
+    const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
+    const char* a = tv + key * ROWB + chunk * 16 + v_within;
+    return __builtin_bit_cast(u32x2,
+                              __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a));
   };
-  auto mma_scores = [&](const u32x4* kf, f32x16* s) {
-    mma_scores_cb(kf, 0, s);
-    mma_scores_cb(kf, 1, s);
+  // MFMA i of the value product of one 32-key block: operand i/2, query column block i%2.
+  constexpr int NPV = 4 * DB;  // MFMAs of one value product; also the transposing reads of one V block
+  auto pv_mfma = [&](auto ic, const u32x2* vh, u32x4 (*pf)[2]) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int m = i / 2, cb = i % 2, db = m / 2, s2 = m % 2;
+    u32x4 f;
+    f[0] = vh[2 * m][0];
+    f[1] = vh[2 * m][1];
+    f[2] = vh[2 * m + 1][0];
+    f[3] = vh[2 * m + 1][1];
+    acc[db][cb] = PElem<DT>::mfma(f, pf[cb][s2], acc[db][cb]);
   };
+  auto zero = [](f32x16& x) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = 0.f;
+  };
+  // S^T block (32 keys x 64 rows) = K Q^T.
   auto scores = [&](const char* tk, int kb, f32x16* s) {
-    u32x4 kf[KS];
-    load_k(tk, kb, kf);
-    mma_scores(kf, s);
+    zero(s[0]);
+    zero(s[1]);
+    static_for<0, KS>([&](auto ks) {
+      const u32x4 kf = read_k(ks, tk, kb);
+      s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
+      s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
+    });
   };
-  // Softmax weights of a score block against the current reference maxima, rounded to the storage type (they
-  // are the MFMA operand), and their sum added to the running sums.  The sum is taken over the rounded weights,
-  // two per instruction (dot product of a packed pair with ones): the normaliser then matches the numerator
-  // exactly, and the adds cost half as many instructions.
-  auto weights_cb = [&](const f32x16* s, int cb, u32x4 (*pf)[2]) {
-    float pr[16];
-    const float nm = -m_used[cb];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cb][i], c, nm));
-    pf[cb][0] = PElem<DT>::pack8(pr);
-    pf[cb][1] = PElem<DT>::pack8(pr + 8);
-    float psum = 0.f, psum2 = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      psum = PElem<DT>::add_pair(pf[cb][0][w], psum);
-      psum2 = PElem<DT>::add_pair(pf[cb][1][w], psum2);
+  // One of the nine steps that turn a 32-key x 32-row score block (16 values per lane) into softmax weights
+  // against the current reference maximum: step j < 8 computes weights 2j and 2j+1, step j >= 1 rounds the
+  // previous pair to the storage type (they are the MFMA operand), stores it as word j-1 of the operand and
+  // adds it to the partial sum.  The sum is taken over the rounded weights, two per instruction (dot product
+  // of the packed pair with ones): the normaliser then matches the numerator exactly.
+  // With a mask, value e of the block (key row 8*(e/4) + e%4 past the lane's first row) only counts when that
+  // offset does not exceed thr.
+  auto weight_step = [&](auto jc, const f32x16& sv, float nm, float* pr, u32x4* pw, float& ps, auto masked,
+                         int thr) {
+    constexpr int j = decltype(jc)::value;
+    if constexpr (j < 8) {
+      pr[2 * j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], c, nm));
+      pr[2 * j + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], c, nm));
+      if constexpr (decltype(masked)::value) {
+        constexpr int e0 = 2 * j, e1 = 2 * j + 1;
+        pr[e0] = 8 * (e0 / 4) + e0 % 4 <= thr ? pr[e0] : 0.f;
+        pr[e1] = 8 * (e1 / 4) + e1 % 4 <= thr ? pr[e1] : 0.f;
+      }
     }
-    l_run[cb] += psum + psum2;
+    if constexpr (j >= 1) {
+      const unsigned w = PElem<DT>::pack2(pr[2 * j - 2], pr[2 * j - 1]);
+      pw[(j - 1) / 4][(j - 1) % 4] = w;
+      ps = PElem<DT>::add_pair(w, ps);
+    }
   };
   auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
-    weights_cb(s, 0, pf);
-    weights_cb(s, 1, pf);
-  };
-  // V^T operands of block kb (one per (d block, 16-key step)), and O^T += V^T P^T: 4*DB MFMAs.
-  auto load_v_part = [&](const char* tv, int kb, u32x4* vf, int db0, int db1) {
 #pragma unroll
-    for (int db = db0; db < db1; ++db)
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        s16x4 h[2];
-#pragma unroll
-        for (int h4 = 0; h4 < 2; ++h4) {
-          const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
-          const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
-          const char* a = tv + key * ROWB + chunk * 16 + v_within;
-          h[h4] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a);
-        }
-        const u32x2 lo = __builtin_bit_cast(u32x2, h[0]), hi2 = __builtin_bit_cast(u32x2, h[1]);
-        u32x4 f;
-        f[0] = lo[0];
-        f[1] = lo[1];
-        f[2] = hi2[0];
-        f[3] = hi2[1];
-        vf[2 * db + s2] = f;
-      }
-  };
-  auto load_v = [&](const char* tv, int kb, u32x4* vf) { load_v_part(tv, kb, vf, 0, DB); };
-  auto mma_values = [&](const u32x4* vf, u32x4 (*pf)[2]) {
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        acc[db][0] = PElem<DT>::mfma(vf[2 * db + s2], pf[0][s2], acc[db][0]);
-        acc[db][1] = PElem<DT>::mfma(vf[2 * db + s2], pf[1][s2], acc[db][1]);
-      }
-  };
-  auto values = [&](const char* tv, int kb, u32x4 (*pf)[2]) {
-    u32x4 vf[2 * DB];
-    load_v(tv, kb, vf);
-    mma_values(vf, pf);
+    for (int cb = 0; cb < 2; ++cb) {
+      float pr[16], ps = 0.f;
+      // (a row that has seen no key yet - possible when a piece starts on the causal diagonal - has no maximum;
+      // its scores are all -inf and must give weight 0, not exp2(-inf + inf))
+      const float nm = m_used[cb] == -INFINITY ? 0.f : -m_used[cb];
+      static_for<0, 9>([&](auto j) { weight_step(j, s[cb], nm, pr, pf[cb], ps, std::false_type{}, 0); });
+      l_run[cb] += ps;
+    }
   };
   // Column maxima of a score block (over the lane's 16 keys and its partner half), in exp2 units.
   auto block_max = [&](const f32x16* s, float* tmax) {
@@ -409,79 +524,32 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 
   // Waits until at most `n` of this wavefront's global-to-LDS loads are outstanding.
   auto wait_loads = [](auto n) {
-    constexpr int N = decltype(n)::value;
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+    constexpr int NW = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (NW & 15) | ((NW >> 4) << 14));
   };
   constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
-  // Tile pipeline.  Tile t lives in buffer t % 4.  While tile kt is computed, tiles kt+1 and kt+2 are in flight
-  // or landed.  Every tile kt follows the same protocol.  Before its synchronisation point it issues loads
-  // 1 and 2 of tile kt+2 (only load 1 when a tile has two loads per tensor).  At the synchronisation point the
-  // wavefront waits until its own part of tile kt+1 has landed - loads complete in order, so it waits until at
-  // most the SYNC_N loads issued after that tile's last one are outstanding - then, past the barrier, everyone's
-  // part has landed and everyone is done with tile kt-1.  After it, it issues the last load of tile kt+2 (when
-  // there are four) and load 0 of tile kt+3, which goes into the buffer of tile kt-1.  Past the last tile the
-  // refills repeat tile nkt-1 (into buffers nobody reads), which keeps the count of outstanding loads, and with
-  // it the wait, the same on every tile.  The barrier is the bare instruction: the fence of __syncthreads
-  // would wait for all outstanding loads.
+  // Tile pipeline.  Tile kt of the piece lives in buffer (kt - s0) % 4.  While tile kt is computed, tiles kt+1
+  // and kt+2 are in flight or landed.  Every tile kt follows the same protocol.  Before its synchronisation
+  // point it issues loads 1 and 2 of tile kt+2 (only load 1 when a tile has two loads per tensor).  At the
+  // synchronisation point the wavefront waits until its own part of tile kt+1 has landed - loads complete in
+  // order, so it waits until at most the SYNC_N loads issued after that tile's last one are outstanding -
+  // then, past the barrier, everyone's part has landed and everyone is done with tile kt-1.  After it, it
+  // issues the last load of tile kt+2 (when there are four) and load 0 of tile kt+3, which goes into the
+  // buffer of tile kt-1.  Past the last tile the refills repeat tile s1-1 (into buffers nobody reads), which
+  // keeps the count of outstanding loads, and with it the wait, the same on every tile.  The barrier is the
+  // bare instruction: the fence of __syncthreads would wait for all outstanding loads.
   constexpr int SYNC_N = NLD > 2 ? VM - 2 : VM;
-  const std::integral_constant<int, 0> part0;
-  const std::integral_constant<int, 1> part1;
-  const std::integral_constant<int, 2> part2;
-  const std::integral_constant<int, 3> part3;
-  auto issue_before_sync = [&](int kt, char* gk, char* gv) {
-    const int t2 = min(kt + 2, nkt - 1);
-    issue_part(part1, t2, gk, gv);
-    if constexpr (NLD > 2) issue_part(part2, t2, gk, gv);
-  };
   auto sync_next = [&]() {
     wait_loads(std::integral_constant<int, SYNC_N>{});
     __builtin_amdgcn_s_barrier();
   };
-  auto issue_after_sync = [&](int kt, char* gk, char* gv, char* fk, char* fv) {
-    if constexpr (NLD > 2) issue_part(part3, min(kt + 2, nkt - 1), gk, gv);
-    issue_part(part0, min(kt + 3, nkt - 1), fk, fv);
+  auto issue_before_sync = [&](const Tile& t2, char* gk) {
+    issue_part(part1, t2, gk, gk + TILEB);
+    if constexpr (NLD > 2) issue_part(part2, t2, gk, gk + TILEB);
   };
-
-  // One of the nine steps that turn a 32-key x 32-row score block (16 values per lane) into weights: step
-  // j < 8 computes weights 2j and 2j+1, step j >= 1 packs the previous pair into word j-1 of the MFMA operand
-  // and adds the pair (as rounded) to the partial sum.
-  auto weight_step = [&](auto jc, const f32x16& sv, float nm, float* pr, u32x4* pw, float& ps) {
-    constexpr int j = decltype(jc)::value;
-    if constexpr (j < 8) {
-      pr[2 * j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], c, nm));
-      pr[2 * j + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], c, nm));
-    }
-    if constexpr (j >= 1) {
-      const unsigned w = PElem<DT>::pack2(pr[2 * j - 2], pr[2 * j - 1]);
-      pw[(j - 1) / 4][(j - 1) % 4] = w;
-      ps = PElem<DT>::add_pair(w, ps);
-    }
-  };
-  // One transposing read of a V^T operand half: read r of block kb covers d block r/4, 16-key step (r/2)%2,
-  // 8-key half r%2; operand 2*db + s2 is the pair of reads 2m, 2m+1.
-  auto read_v = [&](auto rc, const char* tv, int kb) -> u32x2 {
-    constexpr int r = decltype(rc)::value;
-    constexpr int db = r / 4, s2 = (r / 2) % 2, h4 = r % 2;
-    const int key = 32 * kb + 16 * s2 + 8 * h4 + v_key_lane;
-    const int chunk = (4 * db + v_chunk_lane) ^ (4 * ((key / RPL) % (CH / 4)));
-    const char* a = tv + key * ROWB + chunk * 16 + v_within;
-    return __builtin_bit_cast(u32x2,
-                              __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a));
-  };
-  auto read_k = [&](auto ksc, const char* tk, int kb) -> u32x4 {
-    constexpr int ks = decltype(ksc)::value;
-    return *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
-  };
-  // MFMA i of the value product of one 32-key block: operand i/2, query column block i%2.
-  auto pv_mfma = [&](auto ic, const u32x2* vh, u32x4 (*pf)[2]) {
-    constexpr int i = decltype(ic)::value;
-    constexpr int m = i / 2, cb = i % 2, db = m / 2, s2 = m % 2;
-    u32x4 f;
-    f[0] = vh[2 * m][0];
-    f[1] = vh[2 * m][1];
-    f[2] = vh[2 * m + 1][0];
-    f[3] = vh[2 * m + 1][1];
-    acc[db][cb] = PElem<DT>::mfma(f, pf[cb][s2], acc[db][cb]);
+  auto issue_after_sync = [&](const Tile& t2, const Tile& t3, char* gk, char* fk) {
+    if constexpr (NLD > 2) issue_part(part3, t2, gk, gk + TILEB);
+    issue_part(part0, t3, fk, fk + TILEB);
   };
 
   // Fast tile: every (row, key) pair visible, reference maxima fixed.  The instruction order is fixed by hand:
@@ -497,58 +565,61 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   //   E  O += V(block 0) P(block 0)     | weights of D's scores, reads V block 1
   //   -- synchronisation point --
   //   F  O += V(block 1) P(block 1)     | issues loads of tiles kt+2 / kt+3, reads K block 0 of the next tile
-  // ck/cv: this tile; nk: K of the next tile; gk/gv: buffer of tile kt+2; fk/fv: buffer of tile kt+3.  k0 holds K
-  // block 0 of this tile on entry and of the next tile on exit.
-  constexpr int NPV = 4 * DB;  // MFMAs of one value product; also the transposing reads of one V block
+  // ck: this tile's buffer (K, then V); nk: the next tile's; gk: buffer of tile kt+2; fk: buffer of tile kt+3.
+  // k0 holds K block 0 of this tile on entry and of the next tile on exit; t2 describes tile kt+2 on entry and
+  // tile kt+3 (the next tile's kt+2) on exit.
   static_assert(NPV == 2 * KS, "V reads are spread one per slot over two score stages");
-  auto fast_tile = [&](int kt, const char* ck, const char* cv, const char* nk, char* gk, char* gv, char* fk,
-                       char* fv, u32x4* k0) {
-    f32x16 s0[2], s1[2];
+  auto fast_tile = [&](auto masked, int kt, const char* ck, const char* nk, char* gk, char* fk, u32x4* k0, Tile& t2) {
+    f32x16 s0v[2], s1v[2];
     u32x4 p0[2][2], p1[2][2];
     u32x4 k1[KS];
     u32x2 v0h[NPV], v1h[NPV];
     float pr[16], ps;
     const float nm0 = -m_used[0], nm1 = -m_used[1];
-    const int t2 = min(kt + 2, nkt - 1);
-    auto zero = [](f32x16& x) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) x[i] = 0.f;
-    };
+    const char* cv = ck + TILEB;
+    // masked variant: rows of the tile the two query rows of the lane see, as offsets from the lane's first row
+    // of key block 0 (block 1 is 32 further)
+    int thr0 = 0, thr1 = 0;
+    if constexpr (decltype(masked)::value) {
+      const Tile cur = tile_of(kt);
+      thr0 = min(lim[0] - cur.jbase, cur.last_row) - 4 * hi;
+      thr1 = min(lim[1] - cur.jbase, cur.last_row) - 4 * hi;
+    }
     // A
-    zero(s0[0]);
+    zero(s0v[0]);
     static_for<0, KS>([&](auto i) {
-      s0[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0[0]);
+      s0v[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0v[0]);
       k1[i] = read_k(i, ck, 1);
-      if constexpr (i == 0) issue_part(part1, t2, gk, gv);
-      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk, gv);
+      if constexpr (i == 0) issue_part(part1, t2, gk, gk + TILEB);
+      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk, gk + TILEB);
       __builtin_amdgcn_sched_barrier(0);
     });
     // B
-    zero(s0[1]);
+    zero(s0v[1]);
     ps = 0.f;
     static_for<0, KS>([&](auto i) {
-      s0[1] = PElem<DT>::mfma(k0[i], qf[1][i], s0[1]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0[0], nm0, pr, p0[0], ps); });
+      s0v[1] = PElem<DT>::mfma(k0[i], qf[1][i], s0v[1]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[0], nm0, pr, p0[0], ps, masked, thr0); });
       v0h[i] = read_v(i, cv, 0);
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run[0] += ps;
     // C
-    zero(s1[0]);
+    zero(s1v[0]);
     ps = 0.f;
     static_for<0, KS>([&](auto i) {
-      s1[0] = PElem<DT>::mfma(k1[i], qf[0][i], s1[0]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0[1], nm1, pr, p0[1], ps); });
+      s1v[0] = PElem<DT>::mfma(k1[i], qf[0][i], s1v[0]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[1], nm1, pr, p0[1], ps, masked, thr1); });
       v0h[KS + i] = read_v(std::integral_constant<int, KS + i>{}, cv, 0);
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run[1] += ps;
     // D
-    zero(s1[1]);
+    zero(s1v[1]);
     ps = 0.f;
     static_for<0, KS>([&](auto i) {
-      s1[1] = PElem<DT>::mfma(k1[i], qf[1][i], s1[1]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s1[0], nm0, pr, p1[0], ps); });
+      s1v[1] = PElem<DT>::mfma(k1[i], qf[1][i], s1v[1]);
+      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s1v[0], nm0, pr, p1[0], ps, masked, thr0 - 32); });
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run[0] += ps;
@@ -556,31 +627,35 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     ps = 0.f;
     static_for<0, NPV>([&](auto i) {
       pv_mfma(i, v0h, p0);
-      static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1[1], nm1, pr, p1[1], ps); });
+      static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1v[1], nm1, pr, p1[1], ps, masked, thr1 - 32); });
       v1h[i] = read_v(i, cv, 1);
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run[1] += ps;
     sync_next();
     // F
+    const Tile t3 = tile_of(min(kt + 3, s1 - 1));
     static_for<0, NPV>([&](auto i) {
       pv_mfma(i, v1h, p1);
       if constexpr (i < KS) k0[i] = read_k(i, nk, 0);
-      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk, gv);
-      if constexpr (i == NPV / 2) issue_part(part0, min(kt + 3, nkt - 1), fk, fv);
+      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk, gk + TILEB);
+      if constexpr (i == NPV / 2) issue_part(part0, t3, fk, fk + TILEB);
       __builtin_amdgcn_sched_barrier(0);
     });
+    t2 = t3;
   };
 
-  auto buf_k = [&](int t) -> char* {
-    const int m = t & 3;
+  auto buf_of = [&](int i) -> char* {
+    const int m = i & 3;
     return m == 0 ? lds_t0 : (m == 1 ? lds_t1 : (m == 2 ? lds_t2 : lds_t3));
   };
-  auto buf_v = [&](int t) -> char* { return buf_k(t) + TILEB; };
 
-  // Generic tile: causal mask, classic online softmax (reference maxima follow the data, accumulators
-  // rescaled when a maximum moves by more than kTau).
-  auto generic_tile = [&](const char* tk, const char* tv, int j0) {
+  // Generic tile: masked (ragged end of a segment, causal diagonal), classic online softmax (reference maxima
+  // follow the data, accumulators rescaled when a maximum moves by more than kTau).  Row r of the tile is
+  // visible to a query row iff it exists and its position jbase + r does not exceed the row's limit.
+  auto generic_tile = [&](const char* tk, const Tile& tl) {
+    const char* tv = tk + TILEB;
+    const int vis0 = min(lim[0] - tl.jbase, tl.last_row), vis1 = min(lim[1] - tl.jbase, tl.last_row);
 #pragma unroll 1
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 s[2];
@@ -589,8 +664,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int j = j0 + 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
-          s[cb][i] = j <= lim[cb] ? s[cb][i] : -INFINITY;
+          const int r = 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
+          s[cb][i] = r <= (cb ? vis1 : vis0) ? s[cb][i] : -INFINITY;
         }
       float tmax[2];
       block_max(s, tmax);
@@ -600,8 +675,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         // only other code that touches them, so it goes through explicit moves.
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-          const float m_new = (cb ? grow1 : grow0) ? tmax[cb] : m_used[cb];
-          const float alpha = __builtin_amdgcn_exp2f(m_used[cb] - m_new);
+          const bool grow = cb ? grow1 : grow0;
+          const float m_new = grow ? tmax[cb] : m_used[cb];
+          // (a row that does not move may still be without a maximum: -inf - -inf must not reach the exponential)
+          const float alpha = grow ? __builtin_amdgcn_exp2f(m_used[cb] - m_new) : 1.0f;
           m_used[cb] = m_new;
           l_run[cb] *= alpha;
 #pragma unroll
@@ -617,63 +694,83 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       }
       u32x4 pf[2][2];
       weights(s, pf);
-      values(tv, kb, pf);
+      u32x2 vh[NPV];
+      static_for<0, NPV>([&](auto r) { vh[r] = read_v(r, tv, kb); });
+      static_for<0, NPV>([&](auto i) { pv_mfma(i, vh, pf); });
     }
   };
 
-  // Tiles whose last key every row of the workgroup may see: kt*64 + 63 <= P + tok0.
-  int nfast = min(nkt, (P + tok0 + 1) / kBN);
+  // Fast tiles of this piece: s0 .. nf-1.
+  int nf = min(s1, nfast_item);
   for (int attempt = 0;; ++attempt) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[db][cb][i] = 0.f;
+      for (int cb = 0; cb < 2; ++cb) zero(acc[db][cb]);
     m_used[0] = m_used[1] = -INFINITY;
     l_run[0] = l_run[1] = 0.f;
 
-    issue_tile(0, lds_t0, lds_t0 + TILEB);
-    issue_tile(min(1, nkt - 1), lds_t1, lds_t1 + TILEB);
-    issue_part(part0, min(2, nkt - 1), lds_t2, lds_t2 + TILEB);
+    issue_tile(tile_of(s0), lds_t0, lds_t0 + TILEB);
+    issue_tile(tile_of(min(s0 + 1, s1 - 1)), lds_t1, lds_t1 + TILEB);
+    Tile t2 = tile_of(min(s0 + 2, s1 - 1));
+    issue_part(part0, t2, lds_t2, lds_t2 + TILEB);
     wait_loads(std::integral_constant<int, VM + 2>{});
     __builtin_amdgcn_s_barrier();
-    int kt = 0;
-    if (nfast > 0) {
+    // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
+    // the vector registers to the scores, the weights and the in-flight LDS operand reads.  They are pinned
+    // there only now, so that their loads and the first tiles' loads are in flight together.
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
+    int kt = s0;
+    if (kt < nf) {
       // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
       // weights are fp16).  Rows whose later scores outgrow the representable range are caught below.
       u32x4 k0[KS];
-      load_k(lds_t0, 0, k0);
+      static_for<0, KS>([&](auto ks) { k0[ks] = read_k(ks, lds_t0, 0); });
       {
         f32x16 s[2];
         float tmax[2];
-        mma_scores(k0, s);
+        zero(s[0]);
+        zero(s[1]);
+        static_for<0, KS>([&](auto ks) {
+          s[0] = PElem<DT>::mfma(k0[ks], qf[0][ks], s[0]);
+          s[1] = PElem<DT>::mfma(k0[ks], qf[1][ks], s[1]);
+        });
         block_max(s, tmax);
         m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
         m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
       }
       for (;;) {
-        fast_tile(kt, lds_t0, lds_t0 + TILEB, lds_t1, lds_t2, lds_t2 + TILEB, lds_t3, lds_t3 + TILEB, k0);
-        if (++kt >= nfast) break;
-        fast_tile(kt, lds_t1, lds_t1 + TILEB, lds_t2, lds_t3, lds_t3 + TILEB, lds_t0, lds_t0 + TILEB, k0);
-        if (++kt >= nfast) break;
-        fast_tile(kt, lds_t2, lds_t2 + TILEB, lds_t3, lds_t0, lds_t0 + TILEB, lds_t1, lds_t1 + TILEB, k0);
-        if (++kt >= nfast) break;
-        fast_tile(kt, lds_t3, lds_t3 + TILEB, lds_t0, lds_t1, lds_t1 + TILEB, lds_t2, lds_t2 + TILEB, k0);
-        if (++kt >= nfast) break;
+        fast_tile(std::false_type{}, kt, lds_t0, lds_t1, lds_t2, lds_t3, k0, t2);
+        if (++kt >= nf) break;
+        fast_tile(std::false_type{}, kt, lds_t1, lds_t2, lds_t3, lds_t0, k0, t2);
+        if (++kt >= nf) break;
+        fast_tile(std::false_type{}, kt, lds_t2, lds_t3, lds_t0, lds_t1, k0, t2);
+        if (++kt >= nf) break;
+        fast_tile(std::false_type{}, kt, lds_t3, lds_t0, lds_t1, lds_t2, k0, t2);
+        if (++kt >= nf) break;
       }
+      // The masked tiles that follow fast ones keep the fixed reference maxima (every row has one by now) and
+      // the same instruction schedule, with the mask applied to the weights.
+      for (; kt < s1; ++kt)
+        fast_tile(std::true_type{}, kt, buf_of(kt - s0), buf_of(kt - s0 + 1), buf_of(kt - s0 + 2), buf_of(kt - s0 + 3),
+                  k0, t2);
     }
-    for (; kt < nkt; ++kt) {
-      issue_before_sync(kt, buf_k(kt + 2), buf_v(kt + 2));
-      generic_tile(buf_k(kt), buf_v(kt), kt * kBN);
+    for (; kt < s1; ++kt) {
+      issue_before_sync(t2, buf_of(kt - s0 + 2));
+      generic_tile(buf_of(kt - s0), tile_of(kt));
       sync_next();
-      issue_after_sync(kt, buf_k(kt + 2), buf_v(kt + 2), buf_k(kt + 3), buf_v(kt + 3));
+      const Tile t3 = tile_of(min(kt + 3, s1 - 1));
+      issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
+      t2 = t3;
     }
     // drain the repeated refills before anything else is loaded into the buffers
     wait_loads(std::integral_constant<int, 0>{});
-    if (attempt > 0 || nfast == 0) break;
+    if (attempt > 0 || nf <= s0) break;
     // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones:
-    // then some sum or accumulator is no longer finite and the whole workgroup redoes its rows the classic way.
+    // then some sum or accumulator is no longer finite and the whole workgroup redoes the piece the classic way.
     float chk = l_run[0] + l_run[1];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -682,52 +779,144 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) chk += __builtin_fabsf(acc[db][cb][i]);
     if (!__syncthreads_or(!(chk < INFINITY))) break;
-    nfast = 0;
+    nf = s0;
   }
 
-  // The next item is claimed only now: a workgroup that claimed it at the start would sit on it for the whole
-  // current item while others idle at the end of the launch.  The atomic's latency hides behind the stores.
-  if (tid == 0) next_item = (int)atomicAdd(&p.counters[0], 1u);
+  // Nobody reads the tile buffers any more once every wavefront is here; the next piece may then load into them
+  // while this one's results are still on their way out (bare barrier: no wait for the stores below).
+  __builtin_amdgcn_s_barrier();
 
-  // out[row, d] = acc / l.  acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row.
+  // acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row.
+  if (whole) {
+    // out[row, d] = acc / l.  The rows go through LDS (the tile buffers are free now; each wavefront uses its own),
+    // so that the global stores are whole 16-byte pieces of contiguous rows rather than 8 bytes per lane scattered
+    // over 32 rows.
+    constexpr int STG = ROWB + 16;  // staging row stride
+    char* stg = buf_of(wave);
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
-    const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
-    if (!q_valid[cb]) continue;
-    const float inv = 1.0f / l_tot;
-    char* op = p.out + ((size_t)(cu_b + tok0 + q_tok[cb]) * p.hq + (size_t)g * G + q_head[cb]) * ROWB;
+    for (int cb = 0; cb < 2; ++cb) {
+      const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
+      const float inv = 1.0f / l_tot;
+      char* sp = stg + (cb * 32 + col) * STG + 8 * hi;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w;
-        w[0] = PElem<DT>::pack2(acc[db][cb][4 * q4] * inv, acc[db][cb][4 * q4 + 1] * inv);
-        w[1] = PElem<DT>::pack2(acc[db][cb][4 * q4 + 2] * inv, acc[db][cb][4 * q4 + 3] * inv);
-        *(u32x2*)(op + (32 * db + 8 * q4 + 4 * hi) * 2) = w;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = PElem<DT>::pack2(acc[db][cb][4 * q4] * inv, acc[db][cb][4 * q4 + 1] * inv);
+          w[1] = PElem<DT>::pack2(acc[db][cb][4 * q4 + 2] * inv, acc[db][cb][4 * q4 + 3] * inv);
+          *(u32x2*)(sp + (32 * db + 8 * q4) * 2) = w;
+        }
+    }
+    // (LDS operations of one wavefront complete in order: no barrier between the writes above and these reads)
+    const unsigned g_magic = (65536u + (unsigned)G - 1u) / (unsigned)G;  // r / G for r < 256
+    constexpr int RPS = 64 / CH;  // rows per store instruction
+#pragma unroll
+    for (int i = 0; i < 64 / RPS; ++i) {
+      const int rl = i * RPS + lane / CH, ch = lane % CH;
+      const int rr = wave * 64 + rl;
+      const int t = (int)(((unsigned)rr * g_magic) >> 16), head = rr - t * G;
+      const u32x4 v = *(const u32x4*)(stg + rl * STG + ch * 16);
+      if (t < ntok)
+        *(u32x4*)(p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)g * G + head) * ROWB + ch * 16) = v;
+    }
+  } else {
+    // A piece: reference maxima, sums and unnormalised accumulators of all 256 rows go to the slot.
+    float* sl = p.ws + (size_t)slot * piece_floats(D);
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
+      const int r = wave * 64 + cb * 32 + col;
+      if (hi == 0) {
+        sl[r] = m_used[cb];
+        sl[256 + r] = l_tot;
       }
-  }
-  // next item (the barriers also keep the LDS tiles of this item safe from the next item's loads)
-  __syncthreads();
-  if (tid == 0) s_item = next_item;
-  __syncthreads();
-  item = __builtin_amdgcn_readfirstlane(s_item);
-  }  // item loop
-
-  // Leave the counters at zero for the next launch: the last workgroup out resets them.
-  if (tid == 0) {
-    const unsigned old = atomicAdd(&p.counters[1], 1u);
-    if (old == gridDim.x - 1) {
-      p.counters[0] = 0u;
-      p.counters[1] = 0u;
+      float* ap = sl + 512 + (size_t)r * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 w;
+          w[0] = acc[db][cb][4 * q4];
+          w[1] = acc[db][cb][4 * q4 + 1];
+          w[2] = acc[db][cb][4 * q4 + 2];
+          w[3] = acc[db][cb][4 * q4 + 3];
+          *(f32x4*)(ap + 32 * db + 8 * q4 + 4 * hi) = w;
+        }
     }
   }
+  }  // piece loop
+  if (tid == 0) shared_items[blockIdx.x] = my_shared;
+}
+
+// Merges the pieces of every item that is shared between workgroups.  Workgroups (w, y) of this kernel look at
+// the record workgroup w of the main kernel left: if an item began in its range and ended in a later one, they
+// merge its pieces - the first one in slot 2w+1, then slot 2u of every following workgroup u that owns tiles of
+// it - for rows 32y .. 32y+31.  With maxima m_p, sums l_p and accumulators a_p of the pieces and M = max m_p:
+// out = sum_p a_p 2^(m_p - M) / sum_p l_p 2^(m_p - M).
+template <int DT, int D>
+__global__ __launch_bounds__(256) void prefill_combine_kernel(PrefillParams p) {
+  const int tid = threadIdx.x;
+  const uint32_t w = blockIdx.x;
+  const SharedItem it = ((const SharedItem*)(p.ws + (size_t)2 * p.n_groups * piece_floats(D)))[w];
+  if (!it.valid) return;
+  ItemShape sh;
+  sh.nkt = it.nkt;
+  sh.nfast = it.nfast;
+  const uint32_t cost = item_cost(sh);
+  const int G = (int)p.group, tb = (int)p.tb;
+  const int cu_b = p.cu[it.b], N = p.cu[it.b + 1] - cu_b;
+  const int tok0 = it.t * tb, ntok = min(tb, N - tok0);
+  // A thread merges 16 consecutive d of one row (four float4); blockIdx.y picks the rows.
+  constexpr int TPR = D / 16;        // threads per row
+  constexpr int RPB = 256 / TPR;     // rows per workgroup
+  const int r = (int)blockIdx.y * RPB + tid / TPR, d0 = 16 * (tid % TPR);
+  const int t = r / G, head = r - t * G;
+  if (t >= ntok) return;
+  float M = -INFINITY, den = 0.f;
+  f32x4 num[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) num[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // two passes over the pieces: the maximum, then the weighted sums
+  for (int pass = 0; pass < 2; ++pass) {
+    for (uint32_t u = w; u < p.n_groups; ++u) {
+      const uint32_t ub = group_begin(p.total_cost, p.n_groups, u), ue = group_begin(p.total_cost, p.n_groups, u + 1);
+      const uint32_t c0 = u == w ? 0u : ub - it.cost_begin;
+      const uint32_t c1 = min(cost, ue - it.cost_begin);
+      if (tile_at(sh, c1) > tile_at(sh, c0)) {
+        const float* sl = p.ws + (size_t)(u == w ? 2 * u + 1 : 2 * u) * piece_floats(D);
+        const float m = sl[r];
+        if (pass == 0) {
+          M = fmaxf(M, m);
+        } else {
+          const float wgt = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
+          den += wgt * sl[256 + r];
+          const f32x4* ap = (const f32x4*)(sl + 512 + (size_t)r * D + d0);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) num[k] += ap[k] * wgt;
+        }
+      }
+      if (ue - it.cost_begin >= cost) break;
+    }
+  }
+  const float inv = 1.0f / den;
+  u32x4 o[2];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    o[k / 2][2 * (k % 2)] = PElem<DT>::pack2(num[k][0] * inv, num[k][1] * inv);
+    o[k / 2][2 * (k % 2) + 1] = PElem<DT>::pack2(num[k][2] * inv, num[k][3] * inv);
+  }
+  char* op = p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)it.g * G + head) * (D * 2) + d0 * 2;
+  ((u32x4*)op)[0] = o[0];
+  ((u32x4*)op)[1] = o[1];
 }
 
 }  // namespace
 
 int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   const uint32_t G = a->n_q_heads / a->n_kv_heads;
-  if (G > (uint32_t)kRows) return VT_E_UNSUPPORTED;
+  if (G > (uint32_t)kRows || a->batch > (uint32_t)kMaxPrefillBatch) return VT_E_UNSUPPORTED;
+  if ((uint64_t)a->n_kv_heads * a->head_dim * 2 >= (1u << 24)) return VT_E_UNSUPPORTED;  // 24-bit row offsets
   PrefillParams p;
   p.q = (const char*)a->q_new;
   p.out = (char*)a->out;
@@ -743,26 +932,39 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   p.group = G;
   p.tb = kRows / G;
   p.scale_log2e = a->scale * 1.4426950408889634f;
-  uint64_t tiles = 0;
+  const bool split = a->k_new != nullptr;
+  uint64_t total = 0;
   for (uint32_t b = 0; b < a->batch; ++b) {
-    const uint32_t n = (uint32_t)(a->cu_seqlens_host[b + 1] - a->cu_seqlens_host[b]);
-    tiles += (n + p.tb - 1) / p.tb;
+    const int n = a->cu_seqlens_host[b + 1] - a->cu_seqlens_host[b];
+    if ((int64_t)a->prefix_lens_host[b] + n > 0x3fffffff) return VT_E_UNSUPPORTED;
+    total += (uint64_t)request_cost(a->prefix_lens_host[b], n, (int)p.tb, split) * a->n_kv_heads;
   }
-  if (tiles == 0) return VT_OK;
-  const uint64_t items = tiles * a->n_kv_heads;
-  if (items > 0x7fffffffull || a->batch > (uint32_t)kMaxPrefillBatch || !ctx->counters) return VT_E_UNSUPPORTED;
-  p.counters = (unsigned*)ctx->counters;
+  if (total == 0) return VT_OK;
+  if (total > 0x7fffffffull) return VT_E_UNSUPPORTED;
+  p.total_cost = (uint32_t)total;
+  uint64_t groups = total / kMinCostPerGroup;
+  groups = groups < 1 ? 1 : (groups > (uint64_t)ctx->n_cus ? (uint64_t)ctx->n_cus : groups);
+  p.n_groups = (uint32_t)groups;
+  const uint64_t ws_bytes = 2 * groups * piece_floats((int)a->head_dim) * sizeof(float) + groups * sizeof(SharedItem);
+  int rc = ensure_workspace(ctx, ws_bytes);
+  if (rc != VT_OK) return rc;
+  p.ws = (float*)ctx->ws;
   hipStream_t st = (hipStream_t)stream;
-  dim3 grid((uint32_t)(items < (uint64_t)ctx->n_cus ? items : (uint64_t)ctx->n_cus));
+  const dim3 grid(p.n_groups), cgrid(p.n_groups, a->head_dim / 16), block(256);
   prof_begin(ctx, 1, st);
-  if (a->dtype == VT_BF16 && a->head_dim == 128)
-    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128>), grid, dim3(256), 0, st, p);
-  else if (a->dtype == VT_BF16 && a->head_dim == 64)
-    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 64>), grid, dim3(256), 0, st, p);
-  else if (a->dtype == VT_F16 && a->head_dim == 128)
-    hipLaunchKernelGGL((prefill_kernel<VT_F16, 128>), grid, dim3(256), 0, st, p);
-  else
-    hipLaunchKernelGGL((prefill_kernel<VT_F16, 64>), grid, dim3(256), 0, st, p);
+  if (a->dtype == VT_BF16 && a->head_dim == 128) {
+    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128>), grid, block, 0, st, p);
+    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_BF16, 128>), cgrid, block, 0, st, p);
+  } else if (a->dtype == VT_BF16 && a->head_dim == 64) {
+    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 64>), grid, block, 0, st, p);
+    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_BF16, 64>), cgrid, block, 0, st, p);
+  } else if (a->dtype == VT_F16 && a->head_dim == 128) {
+    hipLaunchKernelGGL((prefill_kernel<VT_F16, 128>), grid, block, 0, st, p);
+    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_F16, 128>), cgrid, block, 0, st, p);
+  } else {
+    hipLaunchKernelGGL((prefill_kernel<VT_F16, 64>), grid, block, 0, st, p);
+    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_F16, 64>), cgrid, block, 0, st, p);
+  }
   prof_end(ctx, st);
   return hipGetLastError() == hipSuccess ? VT_OK : VT_E_DRIVER;
 }

@@ -115,12 +115,17 @@ def test_empty_request_in_batch(ctx):
     check_prefill(ctx, cfg, d, "empty-request")
 
 
-def test_new_rows_already_in_cache_gives_identical_bits(ctx):
+def test_new_rows_already_in_cache_agrees_with_split_sources(ctx):
+    """The new tokens' K/V either come from k_new / v_new or are already appended to the regions.  The two calls
+    tile the keys differently (cached and new rows are tiled separately when they come from two buffers), so the
+    results agree to rounding, not bit for bit; each is checked against the oracle as well."""
     cfg = CONFIGS[3].replace(batch=3, kv_len=(100, 700), new_len=(30, 200))
     d = workloads.prefill_inputs(cfg, seed=41)
     a = check_prefill(ctx, cfg, d, "split-sources", new_in_cache=False)
     b = check_prefill(ctx, cfg, d, "in-cache", new_in_cache=True)
-    np.testing.assert_array_equal(a, b)
+    diff = np.abs(oracle.widen(a, cfg.dtype) - oracle.widen(b, cfg.dtype)).max()
+    say("  max abs difference between the two calls", float(diff))
+    assert diff <= TOL[cfg.dtype] / 2
 
 
 def test_causality_on_gpu(ctx):
@@ -187,9 +192,14 @@ def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
         derr = float(np.abs(w(out) - ref).max())
         say("  decode after extend max abs err", derr)
         assert derr <= TOL[cfg.dtype]
-        # the prefill in "rows already in cache" mode now sees the same keys: identical bits
+        # the prefill in "rows already in cache" mode now sees the same keys (tiled differently: agreement to
+        # rounding, and the same sampled rows against the oracle)
         again = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale, new_in_cache=True)
-        np.testing.assert_array_equal(again, got)
+        assert np.isfinite(w(again)).all()
+        err2 = sampled_rows_check(cfg, d, again)
+        diff = float(np.abs(w(again) - w(got)).max())
+        say("  in-cache prefill sampled rows max abs err", err2, "max abs difference to the first call", diff)
+        assert err2 <= TOL[cfg.dtype] and diff <= TOL[cfg.dtype] / 2
     finally:
         reg.release()
 
