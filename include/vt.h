@@ -203,13 +203,45 @@ typedef struct {
  * Section 6.2.2 (prefix-prefilling kernel).  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024, scale > 0. */
 int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* stream);
 
+/* Integer work decomposition of a prefix-prefill call.  An item is (request, kv head, token tile of
+ * tb = 256 / (n_q_heads / n_kv_heads) new tokens); it sweeps the key tiles (64 keys) it sees.  Cached rows and new
+ * rows are tiled separately when they come from different buffers (new_rows_in_cache = 0), as one run of rows
+ * otherwise.  A tile is "fast" when all its 64 keys exist and every token of the token tile sees them (in the
+ * sweep the fast tiles come first).  Work is counted in cost units - 8 per item, 2 per fast tile, 3 per other
+ * tile - and workgroup w of n_groups owns units [total_cost * w / n_groups, total_cost * (w+1) / n_groups) of
+ * the items laid end to end (by request, kv head, token tile); a tile belongs to the owner of its first unit.
+ * n_groups = clamp(total_cost / 64, 1, compute units).  An item shared by several workgroups is merged by a
+ * second kernel from per-piece workspace slots. */
+typedef struct {
+  uint64_t total_cost;
+  uint64_t n_tiles;
+  uint32_t n_items;
+  uint32_t n_groups;
+  uint64_t workspace_bytes;
+} vt_prefill_plan;
+
+/* One contiguous run of tiles [tile_begin, tile_end) of an item's sweep, computed by one workgroup. */
+typedef struct {
+  uint32_t group, request, kv_head, token_tile;
+  uint32_t tile_begin, tile_end;  /* in sweep order                                                   */
+  uint32_t n_tiles, n_fast;       /* of the whole item                                                */
+} vt_prefill_piece;
+
+/* Computes the plan vt_attn_prefix_prefill will use for these lengths (host arrays as in vt_prefill_args).
+ * pieces (host, may be NULL) receives up to max_pieces pieces in execution order; *n_pieces (may be NULL) their
+ * total number.  Pure host computation; works on host contexts. */
+int vt_plan_prefill(const vt_ctx* ctx, const int32_t* cu_seqlens_host, const int32_t* prefix_lens_host,
+                    uint32_t batch, uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim,
+                    int new_rows_in_cache, vt_prefill_plan* out, vt_prefill_piece* pieces, uint64_t max_pieces,
+                    uint64_t* n_pieces);
+
 /* Pre-sizes the context's workspace so that later attention calls never allocate. */
 int vt_workspace_reserve(vt_ctx* ctx, uint64_t bytes);
 
 /* ---- misc ------------------------------------------------------------------------------------ */
 
 /* Kernel timing for benchmarks.  While enabled, vt_attn_decode brackets its split-pass kernel (which = 0)
- * and vt_attn_prefix_prefill its main kernel (which = 1) with HIP events recorded on the caller's stream.
+ * and vt_attn_prefix_prefill its two kernels (which = 1) with HIP events recorded on the caller's stream.
  * vt_profile_collect waits for the events recorded so far, returns their summed elapsed time and count
  * for `which`, and forgets them.  At most 4096 launches are kept between two collects. */
 int vt_profile_enable(vt_ctx* ctx, int on);

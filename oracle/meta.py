@@ -75,3 +75,81 @@ def prefill_flops(prefix_lens: Sequence[int], new_lens: Sequence[int], n_q_heads
     """Multiply-adds x2 over the unmasked (query, key) pairs only."""
     pairs = sum(int(n) * int(p) + int(n) * (int(n) + 1) // 2 for p, n in zip(prefix_lens, new_lens))
     return 4 * n_q_heads * head_dim * pairs
+
+
+# ---- prefix-prefill work decomposition (this library's own rule, spelled out from its definition) -------------
+
+PREFILL_TILE = 64          # keys per tile
+PREFILL_ROWS = 256         # query rows per workgroup
+PREFILL_COST_ITEM, PREFILL_COST_FAST, PREFILL_COST_MASKED = 8, 2, 3
+PREFILL_MIN_COST_PER_GROUP = 64
+
+
+def prefill_item_tiles(P: int, N: int, t: int, tb: int, split: bool) -> List[bool]:
+    """The key tiles item (token tile t of tb tokens, request with P cached and N new rows) sweeps, in sweep
+    order; True = fast.  The item's tokens sit at new-row positions tok0 .. tok0+ntok-1 and see the cached rows and
+    the new rows up to their own.  When cached and new rows come from two buffers (split) each buffer is tiled from
+    its own row 0; otherwise they are one run of rows.  A tile is fast when all its 64 rows exist and even the
+    first token of the item sees its last row.  Fast tiles are swept first."""
+    tok0 = t * tb
+    ntok = min(tb, N - tok0)
+    assert ntok >= 1
+    vis = tok0 + ntok
+    # each segment: list of absolute key positions
+    segs = [list(range(P)), [P + r for r in range(vis)]] if split else [list(range(P + vis))]
+    first_tok_pos = P + tok0
+    fast, other = [], []
+    for seg in segs:
+        for k0 in range(0, len(seg), PREFILL_TILE):
+            rows = seg[k0:k0 + PREFILL_TILE]
+            is_fast = len(rows) == PREFILL_TILE and rows[-1] <= first_tok_pos
+            (fast if is_fast else other).append(is_fast)
+    return fast + other
+
+
+def prefill_plan(cu_seqlens: Sequence[int], prefix_lens: Sequence[int], n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, split: bool, n_cus: int = 256):
+    """Returns (total_cost, n_tiles, n_items, n_groups, workspace_bytes, pieces) with pieces a list of
+    (group, request, kv_head, token_tile, tile_begin, tile_end) in execution order.
+
+    Items are laid end to end by request, kv head, token tile; an item costs 8 units, then 2 per fast tile and 3 per
+    other tile in sweep order; group w of n owns units [total*w//n, total*(w+1)//n); a tile belongs to the group
+    that owns its first unit; consecutive tiles of an item with the same owner form a piece."""
+    tb = PREFILL_ROWS // (n_q_heads // n_kv_heads)
+    items = []
+    for b in range(len(prefix_lens)):
+        N = int(cu_seqlens[b + 1]) - int(cu_seqlens[b])
+        for g in range(n_kv_heads):
+            for t in range((N + tb - 1) // tb):
+                items.append((b, g, t, prefill_item_tiles(int(prefix_lens[b]), N, t, tb, split)))
+    cost = lambda tiles: PREFILL_COST_ITEM + sum(PREFILL_COST_FAST if f else PREFILL_COST_MASKED for f in tiles)
+    total = sum(cost(it[3]) for it in items)
+    n_tiles = sum(len(it[3]) for it in items)
+    if total == 0:
+        return 0, 0, 0, 0, 0, []
+    n_groups = max(1, min(n_cus, total // PREFILL_MIN_COST_PER_GROUP))
+    bounds = [total * w // n_groups for w in range(n_groups + 1)]
+    import bisect
+    owner = lambda unit: bisect.bisect_right(bounds, unit) - 1
+    pieces = []
+    begin = 0
+    for b, g, t, tiles in items:
+        unit = begin + PREFILL_COST_ITEM
+        run = None
+        for s, f in enumerate(tiles):
+            w = owner(unit)   # the item's 8 fixed units come before its first tile
+            if run is not None and run[0] == w:
+                run[5] = s + 1
+            else:
+                if run is not None:
+                    pieces.append(tuple(run))
+                run = [w, b, g, t, s, s + 1]
+            unit += PREFILL_COST_FAST if f else PREFILL_COST_MASKED
+        if run is not None:
+            pieces.append(tuple(run))
+        begin += cost(tiles)
+    piece_floats = 512 + 256 * head_dim
+    ws = 2 * n_groups * piece_floats * 4 + n_groups * 32
+    # pieces are executed group by group; within a group in item order (which is the order built above)
+    pieces.sort(key=lambda p: p[0])
+    return total, n_tiles, len(items), n_groups, ws, pieces

@@ -52,6 +52,16 @@ class Plan(C.Structure):
                 ("workspace_bytes", C.c_uint64)]
 
 
+class PrefillPlan(C.Structure):
+    _fields_ = [("total_cost", C.c_uint64), ("n_tiles", C.c_uint64), ("n_items", C.c_uint32),
+                ("n_groups", C.c_uint32), ("workspace_bytes", C.c_uint64)]
+
+
+class PrefillPiece(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("group", "request", "kv_head", "token_tile", "tile_begin", "tile_end",
+                                           "n_tiles", "n_fast")]
+
+
 class DecodeArgs(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_uint32), ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32),
                 ("head_dim", C.c_uint32), ("scale", C.c_float), ("q", C.c_void_p), ("out", C.c_void_p),
@@ -83,6 +93,7 @@ _SIGS = {
     "vt_append": [_vp, _vp, _vp, _u64, _u64, _vp],
     "vt_append_batch": [_vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _vp],
     "vt_plan_decode": [_vp, _vp, _u32, _u32, _u32, _u32, C.POINTER(Plan), _vp],
+    "vt_plan_prefill": [_vp, _vp, _vp, _u32, _u32, _u32, _u32, C.c_int, C.POINTER(PrefillPlan), _vp, C.c_uint64, _vp],
     "vt_attn_decode": [_vp, C.POINTER(DecodeArgs), _vp],
     "vt_attn_prefix_prefill": [_vp, C.POINTER(PrefillArgs), _vp],
     "vt_workspace_reserve": [_vp, _u64],
@@ -200,6 +211,25 @@ def vt_plan_decode(ctx: int, kv_lens_host, n_kv_heads: int, n_q_heads: int, head
     _check(lib.vt_plan_decode(ctx, lens.ctypes.data, len(lens), n_kv_heads, n_q_heads, head_dim, C.byref(plan),
                               ns.ctypes.data), "vt_plan_decode")
     return plan, ns
+
+
+def vt_plan_prefill(ctx: int, cu_seqlens_host, prefix_lens_host, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                    new_rows_in_cache: bool = False, want_pieces: bool = False):
+    """Host arrays as in make_prefill_args.  Returns PrefillPlan, or (PrefillPlan, [PrefillPiece, ...])."""
+    import numpy as np
+    cu = np.ascontiguousarray(cu_seqlens_host, dtype=np.int32)
+    pl = np.ascontiguousarray(prefix_lens_host, dtype=np.int32)
+    plan = PrefillPlan()
+    n = C.c_uint64(0)
+    _check(lib.vt_plan_prefill(ctx, cu.ctypes.data, pl.ctypes.data, len(pl), n_q_heads, n_kv_heads, head_dim,
+                               int(new_rows_in_cache), C.byref(plan), None, 0, C.addressof(n)), "vt_plan_prefill")
+    if not want_pieces:
+        return plan
+    arr = (PrefillPiece * max(1, n.value))()
+    _check(lib.vt_plan_prefill(ctx, cu.ctypes.data, pl.ctypes.data, len(pl), n_q_heads, n_kv_heads, head_dim,
+                               int(new_rows_in_cache), C.byref(plan), C.addressof(arr), n.value, C.addressof(n)),
+           "vt_plan_prefill")
+    return plan, list(arr)[: n.value]
 
 
 def make_decode_args(dtype: int, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, scale: float, q, out,

@@ -102,6 +102,16 @@ int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batc
   return VT_OK;
 }
 
+int vt_plan_prefill(const vt_ctx* ctx, const int32_t* cu_seqlens_host, const int32_t* prefix_lens_host, uint32_t batch,
+                    uint32_t n_q_heads, uint32_t n_kv_heads, uint32_t head_dim, int new_rows_in_cache,
+                    vt_prefill_plan* out, vt_prefill_piece* pieces, uint64_t max_pieces, uint64_t* n_pieces) {
+  if (!ok_ctx(ctx) || !out) return VT_E_INVALID;
+  if (batch && (!cu_seqlens_host || !prefix_lens_host)) return VT_E_INVALID;
+  if (batch && cu_seqlens_host[0] != 0) return VT_E_INVALID;
+  return plan_prefill(ctx, cu_seqlens_host, prefix_lens_host, batch, n_q_heads, n_kv_heads, head_dim,
+                      new_rows_in_cache == 0, out, pieces, max_pieces, n_pieces);
+}
+
 int vt_profile_enable(vt_ctx* ctx, int on) {
   if (!ok_ctx(ctx)) return VT_E_INVALID;
   ctx->profile = on != 0;

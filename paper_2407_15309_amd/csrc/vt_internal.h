@@ -67,7 +67,7 @@ struct vt_ctx {
   vt_stats_t st;
   void* ws;
   uint64_t ws_bytes;
-  void* counters;  // 256 zeroed device bytes: work counters of the persistent prefill kernel
+  void* counters;  // 256 zeroed device bytes (spare)
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;
@@ -105,6 +105,9 @@ void prof_end(vt_ctx* ctx, void* stream);
 // Kernel launchers (device code lives in the .hip files).
 int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream);
 int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream);
+int plan_prefill(const vt_ctx* ctx, const int32_t* cu_host, const int32_t* plens_host, uint32_t batch, uint32_t hq,
+                 uint32_t hkv, uint32_t d, bool split, vt_prefill_plan* out, vt_prefill_piece* pieces,
+                 uint64_t max_pieces, uint64_t* n_pieces);
 int launch_append_batch(void* const* k_ptrs, void* const* v_ptrs, const int32_t* kv_lens, const void* k_rows,
                         const void* v_rows, uint32_t batch, uint32_t row_bytes, void* stream);
 

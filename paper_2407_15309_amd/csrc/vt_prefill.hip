@@ -55,7 +55,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 constexpr int kBN = 64;       // keys per tile
 constexpr int kRows = 256;    // query rows per workgroup (4 wavefronts x 64)
 constexpr float kTau = 8.0f;  // lazy-rescale threshold in log2 units
-constexpr int kMinCostPerGroup = 16;  // a workgroup gets at least the work of eight fast tiles
+constexpr int kMinCostPerGroup = 64;  // a workgroup gets at least the work of 32 fast tiles
 
 template <int DT>
 struct PElem;
@@ -913,10 +913,81 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(PrefillParams p) {
 
 }  // namespace
 
+// Host mirror of the kernel's decomposition: same helpers, same order.
+int plan_prefill(const vt_ctx* ctx, const int32_t* cu_host, const int32_t* plens_host, uint32_t batch, uint32_t hq,
+                 uint32_t hkv, uint32_t d, bool split, vt_prefill_plan* out, vt_prefill_piece* pieces,
+                 uint64_t max_pieces, uint64_t* n_pieces) {
+  if (!cu_host || !plens_host || !out || !hq || !hkv || hq % hkv) return VT_E_INVALID;
+  const uint32_t G = hq / hkv;
+  if (G > (uint32_t)kRows || batch > (uint32_t)kMaxPrefillBatch || (d != 64 && d != 128)) return VT_E_UNSUPPORTED;
+  if ((uint64_t)hkv * d * 2 >= (1u << 24)) return VT_E_UNSUPPORTED;  // 24-bit row offsets in the tile loads
+  const int tb = kRows / (int)G;
+  uint64_t total = 0, tiles = 0, items = 0;
+  for (uint32_t b = 0; b < batch; ++b) {
+    const int n = cu_host[b + 1] - cu_host[b], P = plens_host[b];
+    if (n < 0 || P < 0) return VT_E_INVALID;
+    if ((int64_t)P + n > 0x3fffffff) return VT_E_UNSUPPORTED;
+    total += (uint64_t)request_cost(P, n, tb, split) * hkv;
+    for (int t = 0; t * tb < n; ++t) tiles += (uint64_t)item_shape(P, n, t, tb, split).nkt * hkv;
+    items += (uint64_t)((n + tb - 1) / tb) * hkv;
+    if (total > 0x7fffffffull) return VT_E_UNSUPPORTED;
+  }
+  uint64_t groups = total / kMinCostPerGroup;
+  groups = groups < 1 ? 1 : (groups > (uint64_t)ctx->n_cus ? (uint64_t)ctx->n_cus : groups);
+  out->total_cost = total;
+  out->n_tiles = tiles;
+  out->n_items = (uint32_t)items;
+  out->n_groups = total ? (uint32_t)groups : 0;
+  out->workspace_bytes = total ? 2 * groups * piece_floats((int)d) * sizeof(float) + groups * sizeof(SharedItem) : 0;
+  uint64_t count = 0;
+  if ((pieces || n_pieces) && total) {
+    // walk the items once, carving each at the group boundaries that fall inside it
+    uint64_t begin = 0;  // first cost unit of the current item
+    for (uint32_t b = 0; b < batch; ++b) {
+      const int n = cu_host[b + 1] - cu_host[b], P = plens_host[b];
+      for (uint32_t g = 0; g < hkv; ++g)
+        for (int t = 0; t * tb < n; ++t) {
+          const ItemShape sh = item_shape(P, n, t, tb, split);
+          const uint64_t cost = item_cost(sh);
+          // groups whose range intersects [begin, begin + cost)
+          uint32_t w = (uint32_t)(begin * groups / total);  // its range starts at or before `begin`
+          while (group_begin((uint32_t)total, (uint32_t)groups, w + 1) <= begin) ++w;
+          for (; w < groups && group_begin((uint32_t)total, (uint32_t)groups, w) < begin + cost; ++w) {
+            const uint64_t lo = group_begin((uint32_t)total, (uint32_t)groups, w);
+            const uint64_t hi = group_begin((uint32_t)total, (uint32_t)groups, w + 1);
+            const uint32_t c0 = (uint32_t)(lo > begin ? lo - begin : 0);
+            const uint32_t c1 = (uint32_t)(hi < begin + cost ? hi - begin : cost);
+            const int s0 = tile_at(sh, c0), s1 = tile_at(sh, c1);
+            if (s1 <= s0) continue;
+            if (pieces && count < max_pieces) {
+              vt_prefill_piece& pc = pieces[count];
+              pc.group = w;
+              pc.request = b;
+              pc.kv_head = g;
+              pc.token_tile = (uint32_t)t;
+              pc.tile_begin = (uint32_t)s0;
+              pc.tile_end = (uint32_t)s1;
+              pc.n_tiles = (uint32_t)sh.nkt;
+              pc.n_fast = (uint32_t)sh.nfast;
+            }
+            ++count;
+          }
+          begin += cost;
+        }
+    }
+  }
+  if (n_pieces) *n_pieces = count;
+  return VT_OK;
+}
+
 int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   const uint32_t G = a->n_q_heads / a->n_kv_heads;
-  if (G > (uint32_t)kRows || a->batch > (uint32_t)kMaxPrefillBatch) return VT_E_UNSUPPORTED;
-  if ((uint64_t)a->n_kv_heads * a->head_dim * 2 >= (1u << 24)) return VT_E_UNSUPPORTED;  // 24-bit row offsets
+  const bool split = a->k_new != nullptr;
+  vt_prefill_plan plan;
+  int rc = plan_prefill(ctx, a->cu_seqlens_host, a->prefix_lens_host, a->batch, a->n_q_heads, a->n_kv_heads,
+                        a->head_dim, split, &plan, nullptr, 0, nullptr);
+  if (rc != VT_OK) return rc;
+  if (plan.total_cost == 0) return VT_OK;
   PrefillParams p;
   p.q = (const char*)a->q_new;
   p.out = (char*)a->out;
@@ -932,21 +1003,10 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   p.group = G;
   p.tb = kRows / G;
   p.scale_log2e = a->scale * 1.4426950408889634f;
-  const bool split = a->k_new != nullptr;
-  uint64_t total = 0;
-  for (uint32_t b = 0; b < a->batch; ++b) {
-    const int n = a->cu_seqlens_host[b + 1] - a->cu_seqlens_host[b];
-    if ((int64_t)a->prefix_lens_host[b] + n > 0x3fffffff) return VT_E_UNSUPPORTED;
-    total += (uint64_t)request_cost(a->prefix_lens_host[b], n, (int)p.tb, split) * a->n_kv_heads;
-  }
-  if (total == 0) return VT_OK;
-  if (total > 0x7fffffffull) return VT_E_UNSUPPORTED;
-  p.total_cost = (uint32_t)total;
-  uint64_t groups = total / kMinCostPerGroup;
-  groups = groups < 1 ? 1 : (groups > (uint64_t)ctx->n_cus ? (uint64_t)ctx->n_cus : groups);
-  p.n_groups = (uint32_t)groups;
-  const uint64_t ws_bytes = 2 * groups * piece_floats((int)a->head_dim) * sizeof(float) + groups * sizeof(SharedItem);
-  int rc = ensure_workspace(ctx, ws_bytes);
+  p.total_cost = (uint32_t)plan.total_cost;
+  p.n_groups = plan.n_groups;
+  const uint64_t groups = plan.n_groups;
+  rc = ensure_workspace(ctx, plan.workspace_bytes);
   if (rc != VT_OK) return rc;
   p.ws = (float*)ctx->ws;
   hipStream_t st = (hipStream_t)stream;

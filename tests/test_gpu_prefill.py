@@ -110,6 +110,17 @@ def test_edge_lengths(ctx):
     check_prefill(ctx, cfg, d, "edges-mha-f16-d64")
 
 
+def test_one_item_shared_by_many_workgroups(ctx):
+    """A single (request, kv head, token tile) with a long prefix: its key tiles are spread over several workgroups
+    and the merge kernel combines more than two pieces."""
+    cfg, d = with_lens(CONFIGS[3].replace(n_q_heads=4, n_kv_heads=1), [20000], [64], seed=29)
+    plan, pieces = vt.vt_plan_prefill(ctx, d["cu_seqlens"], d["prefix_lens"], 4, 1, 128, want_pieces=True)
+    assert plan.n_items == 1 and len(pieces) == plan.n_groups >= 8
+    check_prefill(ctx, cfg, d, "one-item-many-groups")
+    cfg, d = with_lens(CONFIGS[3].replace(dtype="f16", n_q_heads=2, n_kv_heads=2, head_dim=64), [9000, 5000], [300, 1], seed=30)
+    check_prefill(ctx, cfg, d, "few-items-many-groups-f16-d64")
+
+
 def test_empty_request_in_batch(ctx):
     cfg, d = with_lens(CONFIGS[3], [50, 70, 10], [5, 0, 9])
     check_prefill(ctx, cfg, d, "empty-request")
