@@ -148,6 +148,8 @@ def bench_prefill(vt, torch, ctx, args):
     a = vt.make_prefill_args(vt.DTYPES[cfg.dtype], cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.scale,
                              int(cu[-1]), qn, out, kn, vn, k_ptrs, v_ptrs, torch.from_numpy(cu).cuda(),
                              torch.from_numpy(pl).cuda(), cu, pl)
+    plan = vt.vt_plan_prefill(ctx, cu, pl, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    vt.vt_workspace_reserve(ctx, plan.workspace_bytes)
     try:
         for _ in range(3):
             vt.vt_attn_prefix_prefill(ctx, a, stream)
@@ -172,7 +174,9 @@ def bench_prefill(vt, torch, ctx, args):
     return {"workload": cfg.name, "flops": flops, "ms_per_call": wall / reps * 1e3, "kernel_ms": kms,
             "tflops": flops / (wall / reps) / 1e12, "kernel_tflops": flops / (kms * 1e-3) / 1e12 if launches else None,
             "frac_of_bf16_peak": flops / (kms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if launches else None,
-            "tokens_per_s": int(cu[-1]) / (wall / reps), "new_tokens": int(cu[-1])}
+            "tokens_per_s": int(cu[-1]) / (wall / reps), "new_tokens": int(cu[-1]),
+            "kernels": "prefill_kernel + prefill_combine_kernel (the events bracket both)",
+            "work_groups": int(plan.n_groups), "key_tiles": int(plan.n_tiles), "items": int(plan.n_items)}
 
 
 def cpu_baseline(dec):
@@ -229,8 +233,14 @@ def main():
         print(json.dumps({"copy_bytes": 1 << 30, "copies": 5}), flush=True)
         return
     ctx = vt.vt_init(0, 0, 0)
-    dec = bench_decode(vt, torch, ctx, args)
-    pre = None if args.no_prefill else bench_prefill(vt, torch, ctx, args)
+    # Everything runs on a stream of its own (torch's side streams do not synchronise with the default stream):
+    # the driver's mapping call inside vt_extend waits for the default stream and every stream that synchronises
+    # with it, so on the default stream each newly mapped chunk would drain the GPU queue first.
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        dec = bench_decode(vt, torch, ctx, args)
+        pre = None if args.no_prefill else bench_prefill(vt, torch, ctx, args)
+    torch.cuda.synchronize()
     vt.vt_destroy(ctx)
     cfg = dec["cfg"]
     line = {

@@ -106,6 +106,16 @@ int vt_extend(vt_kv* kv, uint64_t new_len_tokens);
  * returns its status; requests before it stay extended, the failing one is unchanged. */
 int vt_extend_batch(vt_kv* const* kvs /*host [n]*/, const uint64_t* new_lens /*host [n]*/, uint32_t n);
 
+/* Asynchronous extension (paper Section 4.4: allocation runs asynchronously and overlaps computation; Section 5:
+ * the scheduler dispatches the extension for coming tokens ahead of the kernels that need it).  vt_extend_batch_async queues the same work as vt_extend_batch for a worker
+ * thread of the context (requests run in the order queued) and returns at once with a ticket; the arrays are
+ * copied.  vt_extend_wait blocks until that ticket and all earlier ones have run and returns the ticket's status
+ * (VT_OK, or the error vt_extend_batch would have returned; later requests still run).  The driver's mapping calls
+ * wait for the device work queued before them, which stalls a launching thread but not this worker.  The handles
+ * must stay valid until the ticket has been waited for; vt_destroy runs what is still queued. */
+int vt_extend_batch_async(vt_kv* const* kvs, const uint64_t* new_lens, uint32_t n, uint64_t* ticket);
+int vt_extend_wait(vt_ctx* ctx, uint64_t ticket);
+
 /* Prefix Match by aliasing: reserves a new request whose first ceil(n_tokens*row_bytes/chunk) chunks are
  * the SAME physical chunks as `src`'s (mapped a second time, reference counted; no copy, no new
  * memory), and sets its len to n_tokens.  n_tokens*row_bytes must be a multiple of chunk_bytes unless

@@ -92,6 +92,8 @@ _SIGS = {
     "vt_stats": [_vp, C.POINTER(Stats)],
     "vt_append": [_vp, _vp, _vp, _u64, _u64, _vp],
     "vt_append_batch": [_vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _vp],
+    "vt_extend_batch_async": [_vp, _vp, _u32, _vp],
+    "vt_extend_wait": [_vp, _u64],
     "vt_plan_decode": [_vp, _vp, _u32, _u32, _u32, _u32, C.POINTER(Plan), _vp],
     "vt_plan_prefill": [_vp, _vp, _vp, _u32, _u32, _u32, _u32, C.c_int, C.POINTER(PrefillPlan), _vp, C.c_uint64, _vp],
     "vt_attn_decode": [_vp, C.POINTER(DecodeArgs), _vp],
@@ -164,6 +166,20 @@ def vt_extend_batch(kvs: Sequence[int], new_lens: Sequence[int]) -> None:
     a = (_vp * n)(*kvs)
     l = (_u64 * n)(*[int(x) for x in new_lens])
     _check(lib.vt_extend_batch(a, l, n), "vt_extend_batch")
+
+
+def vt_extend_batch_async(kvs: Sequence[int], new_lens: Sequence[int]) -> int:
+    """Queues the extension for the context's worker thread; returns the ticket for vt_extend_wait."""
+    n = len(kvs)
+    a = (_vp * n)(*kvs)
+    l = (_u64 * n)(*[int(x) for x in new_lens])
+    t = C.c_uint64(0)
+    _check(lib.vt_extend_batch_async(a, l, n, C.addressof(t)), "vt_extend_batch_async")
+    return t.value
+
+
+def vt_extend_wait(ctx: int, ticket: int) -> None:
+    _check(lib.vt_extend_wait(ctx, ticket), "vt_extend_wait")
 
 
 def vt_share_prefix(src: int, n_tokens: int, max_tokens: int) -> int:

@@ -1,9 +1,12 @@
 // Internal declarations shared by the translation units of libvt.  Not part of the ABI.
 #pragma once
 
+#include <condition_variable>
 #include <cstdint>
+#include <deque>
 #include <map>
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "vt.h"
@@ -39,6 +42,13 @@ struct ProfEvent {
   int which;
 };
 
+// One queued vt_extend_batch_async request.
+struct ExtendJob {
+  uint64_t ticket;
+  std::vector<vt_kv*> kvs;
+  std::vector<uint64_t> lens;
+};
+
 }  // namespace vt
 
 struct vt_kv {
@@ -71,6 +81,14 @@ struct vt_ctx {
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;
+  // Asynchronous extension (a worker thread that runs queued extensions in order, started on first use).
+  std::mutex amu;
+  std::condition_variable acv_work, acv_done;
+  std::deque<vt::ExtendJob> ajobs;
+  std::map<uint64_t, int> afailed;   // status of the tickets that failed
+  uint64_t anext = 1, adone = 0;     // next ticket to hand out, last ticket finished
+  bool astop = false;
+  std::thread aworker;
 };
 
 constexpr uint32_t VT_CTX_MAGIC = 0x76544358u;

@@ -478,6 +478,13 @@ int vt_destroy(vt_ctx* ctx) {
   if (!ok_ctx(ctx)) return VT_E_INVALID;
   int worst = VT_OK;
   {
+    // queued extensions finish first; then the worker leaves
+    std::unique_lock<std::mutex> lk(ctx->amu);
+    ctx->astop = true;
+  }
+  ctx->acv_work.notify_all();
+  if (ctx->aworker.joinable()) ctx->aworker.join();
+  {
     std::lock_guard<std::mutex> g(ctx->mu);
     if (!ctx->be->is_host()) {
       (void)hipSetDevice(ctx->device);
@@ -536,6 +543,69 @@ int vt_extend_batch(vt_kv* const* kvs, const uint64_t* new_lens, uint32_t n) {
     if (rc != VT_OK) return rc;
   }
   return VT_OK;
+}
+
+// Worker of the asynchronous extension: takes the queued requests in order and runs them like vt_extend_batch.
+static void extend_worker(vt_ctx* c) {
+  if (!c->be->is_host()) (void)hipSetDevice(c->device);
+  for (;;) {
+    vt::ExtendJob job;
+    {
+      std::unique_lock<std::mutex> lk(c->amu);
+      c->acv_work.wait(lk, [&] { return c->astop || !c->ajobs.empty(); });
+      if (c->ajobs.empty()) return;  // stop requested and nothing left
+      job = std::move(c->ajobs.front());
+      c->ajobs.pop_front();
+    }
+    int rc = VT_OK;
+    {
+      std::lock_guard<std::mutex> g(c->mu);
+      for (size_t i = 0; i < job.kvs.size() && rc == VT_OK; ++i)
+        rc = ok_kv(job.kvs[i]) ? extend_locked(job.kvs[i], job.lens[i]) : VT_E_INVALID;
+    }
+    {
+      std::lock_guard<std::mutex> lk(c->amu);
+      if (rc != VT_OK) c->afailed[job.ticket] = rc;
+      c->adone = job.ticket;
+    }
+    c->acv_done.notify_all();
+  }
+}
+
+int vt_extend_batch_async(vt_kv* const* kvs, const uint64_t* new_lens, uint32_t n, uint64_t* ticket) {
+  if (!ticket || (n && (!kvs || !new_lens))) return VT_E_INVALID;
+  if (n == 0) {
+    *ticket = 0;
+    return VT_OK;
+  }
+  for (uint32_t i = 0; i < n; ++i)
+    if (!ok_kv(kvs[i]) || kvs[i]->ctx != kvs[0]->ctx) return VT_E_INVALID;
+  vt_ctx* c = kvs[0]->ctx;
+  vt::ExtendJob job;
+  job.kvs.assign(kvs, kvs + n);
+  job.lens.assign(new_lens, new_lens + n);
+  {
+    std::lock_guard<std::mutex> lk(c->amu);
+    if (c->astop) return VT_E_INVALID;
+    if (!c->aworker.joinable()) c->aworker = std::thread(extend_worker, c);
+    job.ticket = c->anext++;
+    *ticket = job.ticket;
+    c->ajobs.push_back(std::move(job));
+  }
+  c->acv_work.notify_one();
+  return VT_OK;
+}
+
+int vt_extend_wait(vt_ctx* ctx, uint64_t ticket) {
+  if (!ok_ctx(ctx)) return VT_E_INVALID;
+  std::unique_lock<std::mutex> lk(ctx->amu);
+  if (ticket >= ctx->anext) return VT_E_INVALID;
+  ctx->acv_done.wait(lk, [&] { return ctx->adone >= ticket; });
+  auto it = ctx->afailed.find(ticket);
+  if (it == ctx->afailed.end()) return VT_OK;
+  int rc = it->second;
+  ctx->afailed.erase(it);
+  return rc;
 }
 
 int vt_share_prefix(vt_kv* src, uint64_t n_tokens, uint64_t max_tokens, vt_kv** dst) {

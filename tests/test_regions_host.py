@@ -277,3 +277,34 @@ def test_attention_on_a_host_context_is_refused(ctx):
     with pytest.raises(vt.VtError) as e:
         vt.vt_attn_decode(ctx, a)
     assert e.value.status == vt.VT_E_UNSUPPORTED
+
+
+def test_asynchronous_extension_runs_in_order_and_reports_status(ctx):
+    """vt_extend_batch_async / vt_extend_wait on the host backend: same end state as the synchronous call, tickets
+    finish in order, a failing request reports its own status and later ones still run."""
+    kvs = [vt.vt_reserve(ctx, 8, 128, vt.VT_BF16, 4096) for _ in range(3)]
+    t1 = vt.vt_extend_batch_async(kvs, [100, 1025, 0])
+    t2 = vt.vt_extend_batch_async(kvs, [2049, 1025, 7])
+    assert t2 == t1 + 1
+    vt.vt_extend_wait(ctx, t2)                      # waits for t1 as well
+    vt.vt_extend_wait(ctx, t1)
+    assert [vt.vt_query(k).len for k in kvs] == [2049, 1025, 7]
+    assert [vt.vt_query(k).chunks_mapped for k in kvs] == [meta.chunks_for_len(n, 8, 128, CHUNK) for n in (2049, 1025, 7)]
+    bad = vt.vt_extend_batch_async(kvs[:1], [5000])  # beyond the reserved range
+    ok = vt.vt_extend_batch_async(kvs[1:2], [1100])
+    with pytest.raises(vt.VtError):
+        vt.vt_extend_wait(ctx, bad)
+    vt.vt_extend_wait(ctx, ok)
+    assert vt.vt_query(kvs[0]).len == 2049 and vt.vt_query(kvs[1]).len == 1100
+    with pytest.raises(vt.VtError):
+        vt.vt_extend_wait(ctx, ok + 10)              # never issued
+    for k in kvs:
+        vt.vt_release(k)
+
+
+def test_destroy_runs_queued_extensions():
+    c = vt.vt_init_host(0, 0)
+    kv = vt.vt_reserve(c, 8, 128, vt.VT_BF16, 4096)
+    for n in range(1, 200):
+        vt.vt_extend_batch_async([kv], [n * 20])
+    vt.vt_destroy(c)                                 # no hang, no crash: the worker drains its queue and leaves
