@@ -330,3 +330,67 @@ def test_prefix_sharing_maps_the_same_chunks_into_a_second_region(ctx):
         if dst is not None:
             vt.vt_release(dst)
         reg.release()
+
+
+def test_extension_overlaps_the_decode_steps(ctx):
+    """Paper Sections 4.4 / 5: memory for coming tokens is extended while the current step computes.  A decode loop
+    on a stream that does not synchronise with the default stream, (a) on regions extended beforehand, (b) with
+    vt_extend_batch inside every step, (c) with the extension queued two steps ahead on the context's worker
+    thread: the three produce identical bits, and the loops that extend take about as long as the one that does
+    not (the mapping calls then run beside the kernels instead of draining the queue first)."""
+    import time
+    cfg = CONFIGS[2].replace(batch=32, kv_len=(1500, 2560))
+    data = workloads.decode_inputs(cfg, seed=123)
+    steps, ahead = 40, 2
+    B, hq, hkv, d = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    lens0 = data["kv_lens"].astype(np.int64)
+    rows = [workloads.step_inputs(cfg, s) for s in range(steps)]
+    results, times, maps = {}, {}, {}
+    side = torch.cuda.Stream()
+    for mode in ("pre", "sync", "async"):
+        with torch.cuda.stream(side):
+            reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=cfg.kv_len[1] + steps + ahead + 1)
+            st = stream()
+            q = dev_bits(data["q"])
+            out = torch.zeros_like(q)
+            outs = []
+            k_rows = [dev_bits(r["k_row"]) for r in rows]
+            v_rows = [dev_bits(r["v_row"]) for r in rows]
+            lens_host = [np.ascontiguousarray((lens0 + s + 1).astype(np.int32)) for s in range(steps + ahead)]
+            lens_dev = [torch.from_numpy(x).cuda() for x in lens_host]
+            args = [vt.make_decode_args(vt.DTYPES[cfg.dtype], B, hq, hkv, d, cfg.scale, q, out, reg.k_ptrs, reg.v_ptrs,
+                                        lens_dev[s], lens_host[s]) for s in range(steps)]
+            plan, _ = vt.vt_plan_decode(ctx, lens_host[steps - 1], hkv, hq, d)
+            vt.vt_workspace_reserve(ctx, plan.workspace_bytes)
+            m0 = vt.vt_stats(ctx).map_calls
+            tickets = {}
+            if mode == "pre":
+                vt.vt_extend_batch(reg.kvs, lens_host[steps - 1].tolist())
+            if mode == "async":
+                for s in range(ahead):
+                    tickets[s] = vt.vt_extend_batch_async(reg.kvs, lens_host[s].tolist())
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(steps):
+                if mode == "sync":
+                    vt.vt_extend_batch(reg.kvs, lens_host[s].tolist())
+                elif mode == "async":
+                    vt.vt_extend_wait(ctx, tickets.pop(s))
+                vt.vt_append_batch(ctx, reg.k_ptrs, reg.v_ptrs, lens_dev[s], k_rows[s], v_rows[s], B, hkv, d, st)
+                vt.vt_attn_decode(ctx, args[s], st)
+                if mode == "async" and s + ahead < steps:
+                    tickets[s + ahead] = vt.vt_extend_batch_async(reg.kvs, lens_host[s + ahead].tolist())
+                if s % 13 == 0 or s == steps - 1:
+                    outs.append(out.clone())
+            torch.cuda.synchronize()
+            times[mode] = (time.perf_counter() - t0) / steps
+            maps[mode] = vt.vt_stats(ctx).map_calls - m0
+            results[mode] = [host_bits(o) for o in outs]
+            reg.release()
+    say("  per step: pre-extended %.1f us, extend in step %.1f us, extend ahead %.1f us; chunks mapped in the loops %s"
+        % (times["pre"] * 1e6, times["sync"] * 1e6, times["async"] * 1e6, maps))
+    assert maps["sync"] == maps["async"] and maps["sync"] >= 10      # the loops really map new chunks
+    for a, b, c in zip(results["pre"], results["sync"], results["async"]):
+        np.testing.assert_array_equal(a, b)
+        np.testing.assert_array_equal(a, c)
+    assert times["sync"] <= 1.25 * times["pre"] and times["async"] <= 1.25 * times["pre"]
