@@ -165,11 +165,12 @@ typedef struct {
 
 /* Integer work decomposition of a decode call ("tape split").  Per KV head, the requests' cached tokens laid
  * end to end form a tape of total = sum_b len_b tokens, cut into segments of span_tokens tokens; one wavefront
- * owns one (segment, kv head).  With slots = the plan target (default 2048 wavefront slots):
- *   n_seg       = max(1, min(slots / n_kv_heads, ceil(total / 32)))
+ * owns one (segment, kv head, sub-group of at most 16 of the head's query heads).  With slots = the plan target
+ * (default 2048 wavefront slots) and U = n_kv_heads * ceil((n_q_heads / n_kv_heads) / 16):
+ *   n_seg       = max(1, min(slots / U, ceil(total / 32)))
  *   span_tokens = round_up(ceil(total / n_seg), 32)
  *   pieces_b    = (T_b + len_b - 1) / span_tokens - T_b / span_tokens + 1,  T_b = tokens of the requests before b
- *   max_splits  = max_b pieces_b;   n_units = ceil(total / span_tokens) * n_kv_heads. */
+ *   max_splits  = max_b pieces_b;   n_units = ceil(total / span_tokens) * U. */
 typedef struct {
   uint32_t span_tokens;
   uint32_t max_splits;
@@ -187,7 +188,7 @@ int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batc
  * Paper: Section 2.1 (decode stage), Section 6.2.1 (decoding kernel).  The context's workspace is grown
  * on demand (growing it synchronises the device once; steady-state calls allocate nothing).
  * Errors: VT_E_INVALID for null pointers, n_q_heads % n_kv_heads != 0 or a host length < 1;
- * VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 16 and batch <= 4096. */
+ * VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 256 and batch <= 4096. */
 int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* args, void* stream);
 
 typedef struct {

@@ -37,9 +37,12 @@ def chunks_for_len(length: int, n_kv_heads: int, head_dim: int, chunk: int = CHU
 
 
 def decode_plan(kv_lens: Sequence[int], n_kv_heads: int,
-                slots: int = PLAN_WAVE_SLOTS) -> Tuple[int, List[int], int, int]:
-    """Returns (segment length, pieces per request, max pieces, n_units)."""
+                slots: int = PLAN_WAVE_SLOTS, n_q_heads: int = 0) -> Tuple[int, List[int], int, int]:
+    """Returns (segment length, pieces per request, max pieces, n_units).  A wavefront carries at most 16 query
+    heads of one KV head, so a segment is worked on by n_kv_heads * ceil(group / 16) wavefronts."""
     total = sum(int(L) for L in kv_lens)
+    group = max(1, n_q_heads // n_kv_heads) if n_q_heads else 1
+    n_kv_heads = n_kv_heads * ((group + 15) // 16)
     n_seg = max(1, min(slots // n_kv_heads, (total + 31) // 32))
     seg_len = (total + n_seg - 1) // n_seg
     seg_len = (seg_len + 31) // 32 * 32

@@ -10,21 +10,23 @@ namespace vt {
 
 constexpr uint64_t kDefaultWaveSlots = 2048;  // 256 CUs x 2 workgroups x 4 wavefronts
 
-// Tape split.  Per KV head the requests' tokens laid end to end form a tape of total = sum_b L_b tokens.  It is
-// cut into n_seg = max(1, min(slots / Hkv, ceil(total / 32))) segments of seg_len = round_up(ceil(total / n_seg), 32)
-// tokens; one wavefront owns one (segment, kv head).  Request b, starting at tape position T_b, is covered by
+// Tape split.  Per KV head the requests' tokens laid end to end form a tape of total = sum_b L_b tokens.  With
+// U = Hkv * ceil(G / 16) wavefronts per segment (a wavefront carries at most 16 query heads of one KV head), it is
+// cut into n_seg = max(1, min(slots / U, ceil(total / 32))) segments of seg_len = round_up(ceil(total / n_seg), 32)
+// tokens; one wavefront owns one (segment, kv head, 16-head sub-group).  Request b, starting at tape position T_b, is covered by
 // pieces_b = (T_b + L_b - 1) / seg_len - T_b / seg_len + 1 segments.
 int plan_decode(uint64_t slots, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
                 DecodePlan* out, int32_t* n_splits_out) {
-  if (!lens || !out || !hkv || !hq || !d) return VT_E_INVALID;
+  if (!lens || !out || !hkv || !hq || !d || hq % hkv) return VT_E_INVALID;
   if (slots == 0) slots = kDefaultWaveSlots;
+  const uint64_t units = (uint64_t)hkv * ((hq / hkv + 15) / 16);
   uint64_t total = 0;
   for (uint32_t b = 0; b < batch; ++b) {
     if (lens[b] < 1) return VT_E_INVALID;
     total += (uint64_t)lens[b];
   }
   if (total > 0x7fffffffull) return VT_E_UNSUPPORTED;
-  uint64_t n_seg = std::min<uint64_t>(slots / hkv, (total + 31) / 32);
+  uint64_t n_seg = std::min<uint64_t>(slots / units, (total + 31) / 32);
   if (n_seg < 1) n_seg = 1;
   uint64_t seg_len = total ? (total + n_seg - 1) / n_seg : 32;
   seg_len = (seg_len + 31) / 32 * 32;
@@ -40,7 +42,7 @@ int plan_decode(uint64_t slots, const int32_t* lens, uint32_t batch, uint32_t hk
   out->seg_len = (uint32_t)seg_len;
   out->n_seg = (uint32_t)n_seg;
   out->max_pieces = mx;
-  out->n_units = (total + seg_len - 1) / seg_len * hkv;
+  out->n_units = (total + seg_len - 1) / seg_len * units;
   out->ws_bytes = decode_workspace_bytes(batch, mx, hq, d);
   return VT_OK;
 }
@@ -159,7 +161,7 @@ int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
   if (!a->q || !a->out || !a->k_ptrs || !a->v_ptrs || !a->kv_lens || !a->kv_lens_host) return VT_E_INVALID;
   if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
   if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
-  if (!supported_dim(a->head_dim) || a->n_q_heads / a->n_kv_heads > 16) return VT_E_UNSUPPORTED;
+  if (!supported_dim(a->head_dim) || a->n_q_heads / a->n_kv_heads > 256) return VT_E_UNSUPPORTED;
   DecodePlan plan;
   int rc = plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, &plan,
                        nullptr);

@@ -92,6 +92,7 @@ struct DecodeParams {
   float* part_l;    // [B][max_pieces][Hq]
   void* out;        // [B][Hq][D]
   uint32_t batch, hq, hkv, group, seg_len, max_pieces, n_seg;
+  uint32_t sub;  // 16-head sub-groups per kv head (1 unless the group has more than 16 query heads)
   float scale_log2e;
 };
 
@@ -180,8 +181,15 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
 
   // This wavefront's (segment, kv head).
   const unsigned w_global = (unsigned)__builtin_amdgcn_readfirstlane((int)(blockIdx.x * kWaves + wave));
-  const int sidx = (int)(w_global / p.hkv);
-  const int g = (int)(w_global - (unsigned)sidx * p.hkv);
+  // A wavefront carries at most 16 query heads (the N dimension of the MFMA).  A group of more than 16 is cut into
+  // sub-groups of 16 that each get a wavefront of their own and read the same K/V head (the four wavefronts of a
+  // workgroup are neighbours in this numbering, so the repeated reads meet in the caches).
+  const unsigned units_per_seg = p.hkv * p.sub;
+  const int sidx = (int)(w_global / units_per_seg);
+  const int gv = (int)(w_global - (unsigned)sidx * units_per_seg);
+  const int g = gv / (int)p.sub;                          // kv head
+  const int h0 = (gv - g * (int)p.sub) * 16;              // first query head of the sub-group inside the group
+  const int n_heads = min(16, (int)p.group - h0);         // query heads this wavefront carries
   const int seg0 = sidx * seg_len;
   if (sidx >= (int)p.n_seg || seg0 >= total) return;
   const int seg1 = min(seg0 + seg_len, total);
@@ -221,11 +229,11 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   float m_run, l_run;
   // Q as the B operand: lane (head c16, slot j) holds d-chunk 4*kk + j of its head; heads >= group are zero.
   auto begin_piece = [&](const Piece& d) {
-    const char* qh = p.q + ((size_t)d.b * p.hq + (size_t)g * p.group + c16) * D * 2;
+    const char* qh = p.q + ((size_t)d.b * p.hq + (size_t)g * p.group + h0 + c16) * D * 2;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       u32x4 z = {0u, 0u, 0u, 0u};
-      qf[kk] = (c16 < (int)p.group) ? *(const u32x4*)(qh + (4 * kk + j) * 16) : z;
+      qf[kk] = (c16 < n_heads) ? *(const u32x4*)(qh + (4 * kk + j) * 16) : z;
     }
 #pragma unroll
     for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -317,8 +325,8 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   auto end_piece = [&](const Piece& d) {
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
-    if (c16 >= (int)p.group) return;
-    const size_t head = (size_t)g * p.group + c16;
+    if (c16 >= n_heads) return;
+    const size_t head = (size_t)g * p.group + h0 + c16;
     if (d.count == 1) {
       // The piece is the whole request: normalise and write the output row.
       const float inv = 1.0f / l_run;
@@ -453,12 +461,13 @@ int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, 
   p.hq = a->n_q_heads;
   p.hkv = a->n_kv_heads;
   p.group = a->n_q_heads / a->n_kv_heads;
+  p.sub = (p.group + 15) / 16;
   p.seg_len = plan.seg_len;
   p.max_pieces = plan.max_pieces;
   p.n_seg = plan.n_seg;
   p.scale_log2e = a->scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
-  const uint64_t waves = (uint64_t)plan.n_seg * a->n_kv_heads;
+  const uint64_t waves = (uint64_t)plan.n_seg * a->n_kv_heads * p.sub;
   const uint32_t blocks = (uint32_t)((waves + kWaves - 1) / kWaves);
   const dim3 cgrid(p.hq, a->batch);
   const bool combine = plan.max_pieces > 1;

@@ -81,6 +81,8 @@ def test_config2_bf16_mha_full(ctx):
 @pytest.mark.parametrize("dtype,hq,hkv,d", [
     ("bf16", 32, 8, 128), ("bf16", 64, 8, 128), ("bf16", 32, 2, 128), ("bf16", 32, 4, 128), ("f16", 32, 8, 128),
     ("bf16", 16, 8, 64), ("f16", 24, 3, 64), ("bf16", 5, 1, 128), ("f16", 6, 6, 128), ("bf16", 14, 7, 64),
+    # groups of more than 16 query heads (multi-query attention with 32 heads, 40 = 16 + 16 + 8, 17 = 16 + 1)
+    ("bf16", 32, 1, 128), ("f16", 40, 1, 64), ("bf16", 64, 2, 128), ("bf16", 34, 2, 128),
 ])
 def test_head_group_shapes(ctx, dtype, hq, hkv, d):
     cfg = CONFIGS[2].replace(dtype=dtype, batch=5, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, kv_len=(1, 700))
@@ -203,7 +205,7 @@ def test_bad_arguments_are_refused(ctx):
               v_ptrs=q, kv_lens=q, kv_lens_host=lens)
     for change, status in ((dict(n_kv_heads=3), vt.VT_E_INVALID), (dict(head_dim=96), vt.VT_E_UNSUPPORTED),
                            (dict(q=None), vt.VT_E_INVALID), (dict(dtype=9), vt.VT_E_INVALID),
-                           (dict(n_q_heads=136, n_kv_heads=8), vt.VT_E_UNSUPPORTED),
+                           (dict(n_q_heads=8 * 257, n_kv_heads=8), vt.VT_E_UNSUPPORTED),
                            (dict(kv_lens_host=np.array([0], np.int32)), vt.VT_E_INVALID)):
         with pytest.raises(vt.VtError) as e:
             vt.vt_attn_decode(ctx, vt.make_decode_args(**dict(ok, **change)), stream())

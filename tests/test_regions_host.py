@@ -262,6 +262,13 @@ def test_plan_decode_matches_the_documented_rule(ctx):
         assert (plan.span_tokens, plan.max_splits, plan.n_units) == (span, mx, units)
         assert ns.tolist() == n_splits
         assert plan.workspace_bytes >= B * mx * hkv * 2 * 130 * 4        # room for every (m, l, acc) partial
+    # groups of more than 16 query heads take ceil(G / 16) wavefronts per (segment, kv head)
+    for hq, hkv in ((32, 1), (40, 1), (64, 2), (34, 2), (32, 2)):
+        lens = rng.integers(100, 5000, size=7).astype(np.int32)
+        plan, ns = vt.vt_plan_decode(ctx, lens, hkv, hq, 128)
+        span, n_splits, mx, units = meta.decode_plan(lens, hkv, n_q_heads=hq)
+        assert (plan.span_tokens, plan.max_splits, plan.n_units, ns.tolist()) == (span, mx, units, n_splits)
+    assert vt.vt_plan_decode(ctx, np.array([64000], np.int32), 1, 32, 128)[0].n_units == 2 * 1000   # 1024 slots -> 1000 x 64
     with pytest.raises(vt.VtError):
         vt.vt_plan_decode(ctx, np.array([5, 0], np.int32), 8, 8, 128)     # empty KV is invalid in decode
     for slots in (8, 64, 100000):
