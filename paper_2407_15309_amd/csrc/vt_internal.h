@@ -77,7 +77,6 @@ struct vt_ctx {
   vt_stats_t st;
   void* ws;
   uint64_t ws_bytes;
-  void* counters;  // 256 zeroed device bytes (spare)
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;
@@ -110,7 +109,7 @@ struct DecodePlan {
 int plan_decode(uint64_t target, const int32_t* lens, uint32_t batch, uint32_t hkv, uint32_t hq, uint32_t d,
                 DecodePlan* out, int32_t* n_splits_out);
 
-// Bytes of device workspace a decode launch needs: counters, per-(request, kv head) flags, partial results.
+// Bytes of device workspace a decode launch needs: the tape prefix sums and the partial results.
 uint64_t decode_workspace_bytes(uint32_t batch, uint32_t max_pieces, uint32_t hq, uint32_t d);
 
 // Grows the context's device workspace to at least `bytes`.

@@ -203,7 +203,6 @@ int make_ctx(vt_ctx** out, Backend* be, int device, uint64_t chunk_bytes, uint64
   std::memset(&c->st, 0, sizeof(c->st));
   c->ws = nullptr;
   c->ws_bytes = 0;
-  c->counters = nullptr;
   c->n_cus = 256;
   c->profile = false;
   *out = c;
@@ -455,12 +454,6 @@ int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_by
   if (!be) return st;
   int rc = make_ctx(out, be, device, chunk_bytes, max_phys_bytes);
   if (rc != VT_OK) return rc;
-  if (hipMalloc(&(*out)->counters, 256) != hipSuccess || hipMemset((*out)->counters, 0, 256) != hipSuccess) {
-    (void)hipGetLastError();
-    vt_destroy(*out);
-    *out = nullptr;
-    return VT_E_OOM;
-  }
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
     (*out)->n_cus = cus;
@@ -509,8 +502,6 @@ int vt_destroy(vt_ctx* ctx) {
     }
     ctx->prof.clear();
     if (ctx->ws) (void)hipFree(ctx->ws);
-    if (ctx->counters) (void)hipFree(ctx->counters);
-    ctx->counters = nullptr;
     ctx->ws = nullptr;
     delete ctx->be;
     ctx->be = nullptr;

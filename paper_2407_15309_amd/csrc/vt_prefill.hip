@@ -65,12 +65,6 @@ struct PElem<VT_BF16> {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
                                                    0, 0);
   }
-  static __device__ __forceinline__ u32x4 pack8(const float* p) {
-    bf16x8 v;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (__bf16)p[e];
-    return __builtin_bit_cast(u32x4, v);
-  }
   static __device__ __forceinline__ unsigned pack2(float a, float b) {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     bf16x2 v = {(__bf16)a, (__bf16)b};
@@ -88,12 +82,6 @@ struct PElem<VT_F16> {
   static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
                                                   0);
-  }
-  static __device__ __forceinline__ u32x4 pack8(const float* p) {
-    f16x8 v;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (_Float16)p[e];
-    return __builtin_bit_cast(u32x4, v);
   }
   static __device__ __forceinline__ unsigned pack2(float a, float b) {
     typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
@@ -175,18 +163,12 @@ struct SharedItem {
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr uniform).
 // Written as assembly so that these loads are invisible to the compiler's wait-count bookkeeping: it would
 // otherwise guard operand reads of the tile buffers with waits for every outstanding load.  The kernel places
-// its own waits (wait_loads) and barriers.  Two address forms: uniform base + 32-bit lane offset, or a 64-bit
-// lane address.  (m0 is written here; nothing else in this file uses it.)
+// its own waits (wait_loads) and barriers.  The address is a uniform base plus a 32-bit lane offset.  (m0 is
+// written here; nothing else in this file uses it.)
 __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(lane_off), "s"(base), "s"(lds_addr)
-               : "memory");
-}
-__device__ __forceinline__ void dma16(const char* lane_addr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
-               : "v"(lane_addr), "s"(lds_addr)
                : "memory");
 }
 // Marks a value that is the same in every lane as such (it then lives in scalar registers).
