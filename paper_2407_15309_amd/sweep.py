@@ -8,6 +8,10 @@
       arithmetic-intensity sweep of Section 3.2)
   p1  prefix-prefill, context 16K, prefix ratio 0.5, batch 1..16        (Section 6.2.2, batch-size sweep)
   p2  prefix-prefill, context 16K, batch 4, prefix ratio 0.1..0.9       (Section 6.2.2, prefix-ratio sweep)
+  m1  memory accounting against the running batch size (Section 6.4 / Section 3.1): physical memory mapped by the
+      regions while the batch grows to 64 requests and shrinks again, against the virtual range reserved and
+      against a static preallocation for the largest batch at the maximum length.  Runs on the host backend
+      (same bookkeeping, no GPU needed): python -m paper_2407_15309_amd.sweep --only m1
 
 K/V values are random bf16 written into VMM-backed regions; the tables give the kernel time (HIP events inside
 the library, average over the repetitions) and the fraction of the HBM (8 TB/s) or dense bf16 MFMA (2.5 PFLOP/s)
@@ -99,18 +103,60 @@ def prefill_case(vt, torch, ctx, batch, context, ratio, hq=32, hkv=8, d=128, rep
     return {"us": us, "tflops": flops / us / 1e6, "P": P, "N": N}
 
 
+def memory_accounting(vt, say):
+    """Llama-2-7B-shaped K/V of one layer (32 KV heads x 128, bf16), lengths uniform in [512, 4096] as in the
+    decode workload, maximum length 4096: requests arrive one by one up to 64, then leave one by one."""
+    hkv, d, max_len, chunk = 32, 128, 4096, 2 << 20
+    rng = np.random.default_rng(2407)
+    lens = rng.integers(512, 4097, size=64)
+    ctx = vt.vt_init_host(chunk, 0)
+    row = hkv * d * 2
+    static = 64 * 2 * max_len * row
+    say("\n### m1: one layer of K/V, 32 KV heads x 128 x bf16, max length 4096, chunk 2 MiB, lengths uniform[512,4096]\n")
+    say("| running batch | tokens | exact bytes | mapped (physical) | reserved (virtual) | static preallocation for 64 x 4096 | mapped / static |")
+    say("|---|---|---|---|---|---|---|")
+    kvs = []
+    def row_of(tag):
+        st = vt.vt_stats(ctx)
+        tok = int(sum(lens[: len(kvs)]))
+        say("| %s | %d | %.1f MiB | %.1f MiB | %.1f MiB | %.1f MiB | %.3f |" % (
+            tag, tok, tok * 2 * row / 2 ** 20, st.mapped_bytes / 2 ** 20, st.reserved_va_bytes / 2 ** 20,
+            static / 2 ** 20, st.mapped_bytes / static))
+    for b in range(64):
+        kv = vt.vt_reserve(ctx, hkv, d, vt.VT_BF16, max_len)
+        vt.vt_extend(kv, int(lens[b]))
+        kvs.append(kv)
+        if b + 1 in (1, 2, 4, 8, 16, 32, 64):
+            row_of(str(b + 1))
+    while kvs:
+        vt.vt_release(kvs.pop())
+        if len(kvs) in (32, 8, 0):
+            st = vt.vt_stats(ctx)
+            say("| %d (after releases; %d chunks idle in the pool, %.1f MiB still allocated) | | | %.1f MiB | %.1f MiB | | |" % (
+                len(kvs), st.chunks_pooled, st.phys_bytes / 2 ** 20, st.mapped_bytes / 2 ** 20, st.reserved_va_bytes / 2 ** 20))
+    vt.vt_trim(ctx, 0)
+    st = vt.vt_stats(ctx)
+    say("| 0 (after vt_trim) | | | %.1f MiB mapped, %.1f MiB allocated | | | |" % (st.mapped_bytes / 2 ** 20, st.phys_bytes / 2 ** 20))
+    vt.vt_destroy(ctx)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--quick", action="store_true", help="fewer points")
-    ap.add_argument("--only", default="d1,d2,d3,p1,p2")
+    ap.add_argument("--only", default="d1,d2,d3,p1,p2,m1")
     args = ap.parse_args()
-    import torch
     import paper_2407_15309_amd as vt
+    only = set(args.only.split(","))
+    say = lambda *a: print(*a, flush=True)
+    if "m1" in only:
+        memory_accounting(vt, say)
+        only.discard("m1")
+    if not only:
+        return
+    import torch
     if not torch.cuda.is_available():
         sys.exit("sweep: no GPU visible; the HIP path has no CPU fallback")
-    only = set(args.only.split(","))
     ctx = vt.vt_init(0, 0, 0)
-    say = lambda *a: print(*a, flush=True)
     with torch.cuda.stream(torch.cuda.Stream()):
         if "d1" in only:
             say("\n### d1: decode, 32/32 heads, head_dim 128, bf16, KV length 16384, batch sweep\n")
