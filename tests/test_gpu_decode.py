@@ -89,6 +89,32 @@ def test_head_group_shapes(ctx, dtype, hq, hkv, d):
     check_decode(ctx, cfg, workloads.decode_inputs(cfg, seed=1000 + hq * 7 + hkv), "shapes")
 
 
+def random_shape(rng):
+    """A seeded draw of (dtype, Hq, Hkv, D): every group size the kernels special-case turns up over the seeds."""
+    dtype = ("bf16", "f16")[int(rng.integers(2))]
+    d = (64, 128)[int(rng.integers(2))]
+    hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    g = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 24]))
+    return dtype, hkv * g, hkv, d
+
+
+def edge_biased_length(rng, unit, hi):
+    """A length in [1, hi]: half the draws sit within 2 of a multiple of `unit` (tile and span edges)."""
+    if rng.integers(2):
+        return int(np.clip(unit * rng.integers(1, max(2, hi // unit + 1)) + rng.integers(-2, 3), 1, hi))
+    return int(rng.integers(1, hi + 1))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_seeded_random_shapes_and_lengths(ctx, seed):
+    rng = np.random.default_rng(9000 + seed)
+    dtype, hq, hkv, d = random_shape(rng)
+    lens = [edge_biased_length(rng, 128, 1500) for _ in range(int(rng.integers(1, 7)))]
+    cfg, data = with_lens(CONFIGS[1].replace(dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d), lens,
+                          seed=700 + seed)
+    check_decode(ctx, cfg, data, "random")
+
+
 def test_edge_lengths_around_tiles_and_spans(ctx):
     lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1023, 1024, 1025]
     cfg, d = with_lens(CONFIGS[2].replace(n_q_heads=8, n_kv_heads=4), lens)

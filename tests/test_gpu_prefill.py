@@ -100,6 +100,20 @@ def test_head_group_shapes(ctx, dtype, hq, hkv, d):
     check_prefill(ctx, cfg, workloads.prefill_inputs(cfg, seed=500 + hq * 3 + hkv), "shapes")
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_seeded_random_shapes_and_lengths(ctx, seed):
+    """Seeded draws of head shapes, batch and (prefix, new) lengths, biased towards the 64-key tile edges."""
+    from test_gpu_decode import edge_biased_length, random_shape
+    rng = np.random.default_rng(9100 + seed)
+    dtype, hq, hkv, d = random_shape(rng)
+    nb = int(rng.integers(1, 5))
+    plens = [int(rng.integers(2)) * edge_biased_length(rng, 64, 700) for _ in range(nb)]
+    nlens = [edge_biased_length(rng, 64, 300) for _ in range(nb)]
+    cfg, data = with_lens(CONFIGS[3].replace(dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d), plens, nlens,
+                          seed=800 + seed)
+    check_prefill(ctx, cfg, data, "random", new_in_cache=bool(seed % 3 == 2))
+
+
 def test_edge_lengths(ctx):
     """No prefix (plain causal attention), single new token (= decode), lengths around the tile sizes."""
     plens = [0, 0, 1, 63, 64, 65, 127, 500, 0, 300, 129]
