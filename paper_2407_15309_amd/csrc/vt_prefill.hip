@@ -94,6 +94,14 @@ struct PElem<VT_F16> {
   }
 };
 
+// Workgroup i of n runs on XCD i % 8.  Position of workgroup i when the workgroups are listed XCD by XCD (all of
+// XCD 0 in launch order, then all of XCD 1, ...): XCD x holds ceil((n - x) / 8) workgroups.
+constexpr uint32_t kXcds = 8;
+__host__ __device__ inline uint32_t xcd_run_index(uint32_t i, uint32_t n) {
+  const uint32_t x = i % kXcds, q = n / kXcds, r = n % kXcds;
+  return x * q + (x < r ? x : r) + i / kXcds;
+}
+
 struct PrefillParams {
   const char* q;
   char* out;
@@ -277,8 +285,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const uint32_t row_bytes = p.hkv * D * 2;
 
   build_prefix(p, s_pre, tid, split_src);
-  uint32_t cursor = group_begin(p.total_cost, p.n_groups, blockIdx.x);
-  const uint32_t range_end = group_begin(p.total_cost, p.n_groups, blockIdx.x + 1);
+  // Which group of the plan this workgroup is.  Workgroups are handed to the 8 XCDs in turn (workgroup i runs on
+  // XCD i mod 8), and neighbouring groups sweep the same K/V rows (consecutive token tiles of one request and KV
+  // head) at about the same time: give each XCD a run of consecutive groups, so that its L2 serves the re-reads.
+  const uint32_t group = xcd_run_index(blockIdx.x, p.n_groups);
+  uint32_t cursor = group_begin(p.total_cost, p.n_groups, group);
+  const uint32_t range_end = group_begin(p.total_cost, p.n_groups, group + 1);
   SharedItem* shared_items = (SharedItem*)(p.ws + (size_t)2 * p.n_groups * piece_floats(D));
   SharedItem my_shared = {};
   const int b_win = cursor < range_end ? find_request(p, s_pre, cursor) : 0;
@@ -309,7 +321,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const bool whole = s0 == 0 && s1 == pos.shape.nkt;
   // A piece that continues an item goes to slot 2w, the first piece of an item that ends in a later range to slot
   // 2w+1 (a workgroup has at most one of each).
-  const uint32_t slot = 2 * blockIdx.x + (s0 > 0 ? 0u : 1u);
+  const uint32_t slot = 2 * group + (s0 > 0 ? 0u : 1u);
   if (!whole && s0 == 0) {
     my_shared.valid = 1;
     my_shared.cost_begin = piece_cursor - pos.c;
@@ -828,7 +840,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   }
   }  // piece loop
-  if (tid == 0) shared_items[blockIdx.x] = my_shared;
+  if (tid == 0) shared_items[group] = my_shared;
 }
 
 // Merges the pieces of every item that is shared between workgroups.  Workgroups (w, y) of this kernel look at
