@@ -218,7 +218,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1. "
-                 "Sharding by KV head or by request needs no exchange inside attention; see DESIGN.md.")
+                 "Sharding by KV head or by request would need no exchange inside attention.")
     import torch
     import paper_2407_15309_amd as vt
     if not torch.cuda.is_available():
