@@ -219,10 +219,11 @@ int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* strea
  * rows are tiled separately when they come from different buffers (new_rows_in_cache = 0), as one run of rows
  * otherwise.  A tile is "fast" when all its 64 keys exist and every token of the token tile sees them (in the
  * sweep the fast tiles come first).  Work is counted in cost units - 8 per item, 2 per fast tile, 3 per other
- * tile - and workgroup w of n_groups owns units [total_cost * w / n_groups, total_cost * (w+1) / n_groups) of
+ * tile - and group w of n_groups owns units [total_cost * w / n_groups, total_cost * (w+1) / n_groups) of
  * the items laid end to end (by request, kv head, token tile); a tile belongs to the owner of its first unit.
- * n_groups = clamp(total_cost / 64, 1, compute units).  An item shared by several workgroups is merged by a
- * second kernel from per-piece workspace slots. */
+ * n_groups = clamp(total_cost / 64, 1, compute units).  One workgroup computes one group (which workgroup of the
+ * launch takes which group is the kernel's business: it hands runs of consecutive groups to the same XCD).  An
+ * item shared by several groups is merged by a second kernel from per-piece workspace slots. */
 typedef struct {
   uint64_t total_cost;
   uint64_t n_tiles;
