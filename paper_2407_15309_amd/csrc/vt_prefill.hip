@@ -383,6 +383,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   }
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
+  // Rows past the last token of the tile are padding; a wavefront whose 64 rows are all padding computes nothing.
+  const bool wave_idle = (wave * 64) / G >= ntok;
 
   // Tile loads.  Load i of this wavefront fills LDS rows (NLD*wave + i)*RPI .. +RPI-1 of the tile; the lane
   // lands in row `row` at chunk position ld_pos and therefore fetches the chunk that the swizzle assigns to
@@ -718,7 +720,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
     int kt = s0;
-    if (kt < nf) {
+    if (wave_idle) {
+      // No row of this wavefront belongs to a token (the last token tile of a request is padded to 256 rows): it
+      // only keeps its part of the tile pipeline going - the same loads, waits and barriers per tile as below.
+      for (; kt < s1; ++kt) {
+        issue_before_sync(t2, buf_of(kt - s0 + 2));
+        sync_next();
+        const Tile t3 = tile_of(min(kt + 3, s1 - 1));
+        issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
+        t2 = t3;
+      }
+    } else if (kt < nf) {
       // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
       // weights are fp16).  Rows whose later scores outgrow the representable range are caught below.
       u32x4 k0[KS];
@@ -815,10 +827,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         *(u32x4*)(p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)g * G + head) * ROWB + ch * 16) = v;
     }
   } else {
-    // A piece: reference maxima, sums and unnormalised accumulators of all 256 rows go to the slot.
+    // A piece: reference maxima, sums and unnormalised accumulators of its rows go to the slot (the merge pass
+    // never looks at padding rows).
     float* sl = p.ws + (size_t)slot * piece_floats(D);
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < 2 && !wave_idle; ++cb) {
       const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
       const int r = wave * 64 + cb * 32 + col;
       if (hi == 0) {
