@@ -368,6 +368,15 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     return r;
   };
 
+  // Descriptor for a tile that is loaded ahead of its use.  Past the end of the piece the loads go on (so that the
+  // count of outstanding loads, and with it the wait at every tile, stays the same), into buffers nobody reads:
+  // every lane then fetches from row 0 of the last tile - a few cache lines instead of a tile.
+  auto tile_ahead = [&](int s) -> Tile {
+    Tile r = tile_of(min(s, s1 - 1));
+    r.last_row = s < s1 ? r.last_row : 0;
+    return r;
+  };
+
   // Query rows of this lane (one per 32-column block) and their causal limits.
   int lim[2];
   u32x4 qf[2][KS];
@@ -531,8 +540,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // order, so it waits until at most the SYNC_N loads issued after that tile's last one are outstanding -
   // then, past the barrier, everyone's part has landed and everyone is done with tile kt-1.  After it, it
   // issues the last load of tile kt+2 (when there are four) and load 0 of tile kt+3, which goes into the
-  // buffer of tile kt-1.  Past the last tile the refills repeat tile s1-1 (into buffers nobody reads), which
-  // keeps the count of outstanding loads, and with it the wait, the same on every tile.  The barrier is the
+  // buffer of tile kt-1.  Past the last tile the refills go on as dummies (see tile_ahead), which keeps the count
+  // of outstanding loads, and with it the wait, the same on every tile.  The barrier is the
   // bare instruction: the fence of __syncthreads would wait for all outstanding loads.
   constexpr int SYNC_N = NLD > 2 ? VM - 2 : VM;
   auto sync_next = [&]() {
@@ -630,7 +639,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     l_run[1] += ps;
     sync_next();
     // F
-    const Tile t3 = tile_of(min(kt + 3, s1 - 1));
+    const Tile t3 = tile_ahead(kt + 3);
     static_for<0, NPV>([&](auto i) {
       pv_mfma(i, v1h, p1);
       if constexpr (i < KS) k0[i] = read_k(i, nk, 0);
@@ -707,8 +716,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     l_run[0] = l_run[1] = 0.f;
 
     issue_tile(tile_of(s0), lds_t0, lds_t0 + TILEB);
-    issue_tile(tile_of(min(s0 + 1, s1 - 1)), lds_t1, lds_t1 + TILEB);
-    Tile t2 = tile_of(min(s0 + 2, s1 - 1));
+    issue_tile(tile_ahead(s0 + 1), lds_t1, lds_t1 + TILEB);
+    Tile t2 = tile_ahead(s0 + 2);
     issue_part(part0, t2, lds_t2, lds_t2 + TILEB);
     wait_loads(std::integral_constant<int, VM + 2>{});
     __builtin_amdgcn_s_barrier();
@@ -726,7 +735,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       for (; kt < s1; ++kt) {
         issue_before_sync(t2, buf_of(kt - s0 + 2));
         sync_next();
-        const Tile t3 = tile_of(min(kt + 3, s1 - 1));
+        const Tile t3 = tile_ahead(kt + 3);
         issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
         t2 = t3;
       }
@@ -768,7 +777,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       issue_before_sync(t2, buf_of(kt - s0 + 2));
       generic_tile(buf_of(kt - s0), tile_of(kt));
       sync_next();
-      const Tile t3 = tile_of(min(kt + 3, s1 - 1));
+      const Tile t3 = tile_ahead(kt + 3);
       issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
       t2 = t3;
     }
