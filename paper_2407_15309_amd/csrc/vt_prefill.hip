@@ -21,8 +21,9 @@
 // whole items and at most two pieces of items it shares with its neighbours.  A whole item is normalised
 // and written out at once; a piece leaves its running maxima, sums and unnormalised accumulators in a
 // workspace slot, and a second kernel merges the pieces of every shared item.  Every workgroup gets the same
-// number of tiles whatever the mix of lengths, and a call with fewer items than compute units still fills
-// the chip.
+// amount of work (in cost units: tiles plus a fixed share per item) whatever the mix of lengths, and a call with
+// fewer items than compute units still fills the chip.  Runs of consecutive shares go to the same XCD, whose L2
+// then serves part of the repeated sweeps over one K/V range.
 //
 // Data movement: K and V tiles go from global memory straight into LDS (global_load_lds, 16 B per lane, no
 // registers), four tile buffers, one workgroup barrier per tile.  Both tiles keep their natural [key][d]
@@ -31,9 +32,11 @@
 // V^T operand is read with the transposing LDS read (ds_read_b64_tr_b16): 16 lanes fetch a 4-key x 16-d
 // block and each lane receives the 4 keys of its own d.
 //
-// The running maximum is only refreshed when a tile exceeds it by more than 2^8, which keeps the
-// accumulator rescale off the common path; the final division by the running sum makes the result
-// independent of which reference maximum was used.
+// Softmax: tiles whose 64 keys every row sees ("fast" tiles, swept first) use reference maxima fixed at the start
+// of the piece - no maximum tracking, no rescale; an overflow of the weights is detected once per piece and the
+// piece redone the classic way.  On the classic path the running maximum is only refreshed when a tile exceeds
+// it by more than 2^8, which keeps the accumulator rescale off the common path.  The final division by the
+// running sum makes the result independent of which reference maximum was used.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
