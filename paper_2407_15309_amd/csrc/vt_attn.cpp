@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 
 #include "vt_internal.h"
 
@@ -161,12 +162,12 @@ int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
   if (!a->q || !a->out || !a->k_ptrs || !a->v_ptrs || !a->kv_lens || !a->kv_lens_host) return VT_E_INVALID;
   if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
   if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
+  if (!std::isfinite(a->scale)) return VT_E_INVALID;
   if (!supported_dim(a->head_dim) || a->n_q_heads / a->n_kv_heads > 256) return VT_E_UNSUPPORTED;
   DecodePlan plan;
   int rc = plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, &plan,
                        nullptr);
   if (rc != VT_OK) return rc;
-  if (a->batch > 65535) return VT_E_UNSUPPORTED;
   rc = ensure_workspace(ctx, plan.ws_bytes);
   if (rc != VT_OK) return rc;
   return launch_decode(ctx, a, plan, stream);
@@ -183,7 +184,7 @@ int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) 
   if (!a->n_q_heads || !a->n_kv_heads || a->n_q_heads % a->n_kv_heads) return VT_E_INVALID;
   if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
   if (!supported_dim(a->head_dim)) return VT_E_UNSUPPORTED;
-  if (!(a->scale > 0.0f) || !(a->scale < 3.0e38f)) return VT_E_INVALID;  // the kernel orders scores before scaling
+  if (!std::isfinite(a->scale)) return VT_E_INVALID;
   if (a->cu_seqlens_host[0] != 0 || (uint32_t)a->cu_seqlens_host[a->batch] != a->total_new_tokens) return VT_E_INVALID;
   for (uint32_t b = 0; b < a->batch; ++b)
     if (a->cu_seqlens_host[b + 1] < a->cu_seqlens_host[b] || a->prefix_lens_host[b] < 0) return VT_E_INVALID;

@@ -139,7 +139,9 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   constexpr int CH = T::CH, TPL = T::TPL, NLK = T::NLK;
   constexpr int KK = D / 32;       // MFMA k-steps of the score product
   constexpr int NM = D / 16;       // MFMAs (16 d-rows each) of the value product
-  constexpr int RSB = D * 2 + 16;  // LDS row stride in bytes (16 B pad: conflict-free operand reads)
+  constexpr int RSB = D * 2 + 16;  // LDS row stride in bytes (the 16 B pad spreads the rows of an operand read over the
+                                   // banks; the counters still show conflicts on about half of the LDS instructions,
+                                   // which a kernel that waits for HBM does not feel)
   __shared__ __attribute__((aligned(16))) char lds_all[kWaves][kTile * RSB];
   __shared__ int tape[kMaxDecodeBatch + 1];  // tape[b] = tokens of the requests before b
   __shared__ int wave_tot[kWaves];
@@ -147,14 +149,16 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int B = (int)p.batch, seg_len = (int)p.seg_len;
 
-  // Exclusive prefix sum of the lengths: 16 requests per thread, wavefront scan, then across wavefronts.
+  // Exclusive prefix sum of the lengths, entries 0 .. B (entry B is the tape's total).  Thread t owns the `per`
+  // consecutive entries t*per .. t*per + per - 1 with per = ceil((B + 1) / 256), so the 256 threads cover
+  // 0 .. 256*per - 1 >= B whatever the batch (one entry per thread up to batch 255, 17 at the largest batch);
+  // wavefront scan of the per-thread sums, then across wavefronts.
   {
-    int local[16], sum = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = tid * 16 + i;
-      local[i] = r < B ? p.kv_lens[r] : 0;
-      sum += local[i];
+    const int per = (B + 256) >> 8;
+    int sum = 0;
+    for (int i = 0; i < per; ++i) {
+      const int r = tid * per + i;
+      sum += r < B ? p.kv_lens[r] : 0;
     }
     int incl = sum;
 #pragma unroll
@@ -166,14 +170,13 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
     __syncthreads();
     int base = incl - sum;
     for (int w = 0; w < wave; ++w) base += wave_tot[w];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = tid * 16 + i;
+    for (int i = 0; i < per; ++i) {
+      const int r = tid * per + i;
       if (r <= B) {
         tape[r] = base;
         if (blockIdx.x == 0) p.tape[r] = base;
       }
-      base += local[i];
+      base += r < B ? p.kv_lens[r] : 0;
     }
     __syncthreads();
   }

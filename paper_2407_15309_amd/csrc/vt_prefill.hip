@@ -115,7 +115,8 @@ struct PrefillParams {
   const int32_t* cu;
   const int32_t* plens;
   uint32_t batch, hq, hkv, group, tb;  // tb = new tokens per workgroup = 256 / group
-  float scale_log2e;
+  float scale_log2e;                   // |scale| * log2(e), at least the smallest normal number
+  uint32_t q_sign;                     // 0x80008000 when scale < 0 (the query values are negated instead), else 0
   uint32_t total_cost, n_groups;       // cost units of the whole call, workgroups sharing them
   float* ws;                           // 2 * n_groups piece slots, then n_groups shared-item records
 };
@@ -391,7 +392,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     lim[cb] = P + tok0 + q_tok;                // key j is visible iff j <= lim
     const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok) * p.hq + (size_t)g * G + q_head) * ROWB;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
+    for (int ks = 0; ks < KS; ++ks) {
+      // (a negative scale is applied as |scale| to scores of the negated queries: the kernel takes maxima of raw
+      // scores and multiplies afterwards, which needs a non-negative factor)
+      const u32x4 raw = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
+      qf[cb][ks] = u32x4{raw[0] ^ p.q_sign, raw[1] ^ p.q_sign, raw[2] ^ p.q_sign, raw[3] ^ p.q_sign};
+    }
   }
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
@@ -743,8 +749,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         t2 = t3;
       }
     } else if (kt < nf) {
-      // Reference maxima for the fast tiles: the column maxima of the first 32 keys (plus headroom when the
-      // weights are fp16).  Rows whose later scores outgrow the representable range are caught below.
+      // Reference maxima for the fast tiles: the column maxima of the first 32 keys.  fp16 weights have a short
+      // exponent range (2^-24 .. 2^16), and only an overflow is noticed afterwards (rows whose later scores outgrow
+      // the representable range are caught below), never an underflow: the reference sits 8 units BELOW the maxima,
+      // so that a key as good as the first ones weighs 2^8, later keys may exceed them by 2^8 more before the
+      // fallback is taken, and keys 2^22 times lighter than the first ones still keep every bit.
       u32x4 k0[KS];
       static_for<0, KS>([&](auto ks) { k0[ks] = read_k(ks, lds_t0, 0); });
       {
@@ -757,8 +766,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
           s[1] = PElem<DT>::mfma(k0[ks], qf[1][ks], s[1]);
         });
         block_max(s, tmax);
-        m_used[0] = tmax[0] + (DT == VT_F16 ? 4.0f : 0.0f);
-        m_used[1] = tmax[1] + (DT == VT_F16 ? 4.0f : 0.0f);
+        m_used[0] = tmax[0] - (DT == VT_F16 ? 8.0f : 0.0f);
+        m_used[1] = tmax[1] - (DT == VT_F16 ? 8.0f : 0.0f);
       }
       for (;;) {
         fast_tile(std::false_type{}, kt, lds_t0, lds_t1, lds_t2, lds_t3, k0, t2);
@@ -838,6 +847,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       if (t < ntok)
         *(u32x4*)(p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)g * G + head) * ROWB + ch * 16) = v;
     }
+    // The staging rows lie in tile buffers that every wavefront loads into: nobody may start the next piece's
+    // loads before all staged rows have been read back (the values are in registers by now; the stores go on).
+    __builtin_amdgcn_s_barrier();
   } else {
     // A piece: reference maxima, sums and unnormalised accumulators of its rows go to the slot (the merge pass
     // never looks at padding rows).
@@ -1021,7 +1033,10 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   p.hkv = a->n_kv_heads;
   p.group = G;
   p.tb = kRows / G;
-  p.scale_log2e = a->scale * 1.4426950408889634f;
+  // A zero scale (every visible key weighs the same) runs as the smallest positive one: the scaled scores then vanish
+  // in fp32 and masked keys (minus infinity before scaling) stay masked.
+  p.scale_log2e = std::fmax(std::fabs(a->scale) * 1.4426950408889634f, 1.17549435e-38f);
+  p.q_sign = a->scale < 0.0f ? 0x80008000u : 0u;
   p.total_cost = (uint32_t)plan.total_cost;
   p.n_groups = plan.n_groups;
   const uint64_t groups = plan.n_groups;

@@ -31,13 +31,13 @@ def ctx():
     vt.vt_destroy(c)
 
 
-def oracle_prefill(cfg, d):
+def oracle_prefill(cfg, d, scale=None):
     w = lambda x: oracle.widen(x, cfg.dtype)
     return oracle.prefix_prefill(w(d["q_new"]), w(d["k_new"]), w(d["v_new"]), d["cu_seqlens"],
-                                 [w(x) for x in d["k"]], [w(x) for x in d["v"]], cfg.scale)
+                                 [w(x) for x in d["k"]], [w(x) for x in d["v"]], cfg.scale if scale is None else scale)
 
 
-def check_prefill(ctx, cfg, d, tag, new_in_cache=False):
+def check_prefill(ctx, cfg, d, tag, new_in_cache=False, scale=None):
     say("prefill case", tag, "dtype", cfg.dtype, "B", cfg.batch, "Hq/Hkv", cfg.n_q_heads, cfg.n_kv_heads, "D",
         cfg.head_dim, "P", d["prefix_lens"][:8].tolist(), "N", d["new_lens"][:8].tolist(), "seed", d["seed"],
         "new_in_cache", new_in_cache)
@@ -49,10 +49,11 @@ def check_prefill(ctx, cfg, d, tag, new_in_cache=False):
         k, v = d["k"], d["v"]
     reg = Regions(ctx, k, v, cfg.dtype, headroom=1)
     try:
-        got = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale, new_in_cache)
+        got = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads,
+                          cfg.scale if scale is None else scale, new_in_cache)
     finally:
         reg.release()
-    ref = oracle_prefill(cfg, d)
+    ref = oracle_prefill(cfg, d, scale)
     gv = oracle.widen(got, cfg.dtype)
     assert np.isfinite(gv).all()
     err = np.abs(gv - ref)
@@ -179,7 +180,7 @@ def sampled_rows_check(cfg, d, got, rows_per_request=3):
 
 
 def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
-    """Config 4 at full size: prefix-prefill over 8K-32K token histories (checked on sampled rows, all heads),
+    """Config 4 at full size: prefix-prefill over 8K-32K token histories (every output row against the oracle),
     then vt_extend grows each request by its new turn, the rows are appended, and one decode step runs over
     the extended cache (checked on every output)."""
     cfg = CONFIGS[4]
@@ -190,9 +191,13 @@ def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
         base = reg.k_ptrs.clone()
         got = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale)
         assert np.isfinite(oracle.widen(got, cfg.dtype)).all()
-        err = sampled_rows_check(cfg, d, got)
-        say("  prefill sampled rows max abs err", err)
+        say("  oracle over all", int(d["cu_seqlens"][-1]), "new tokens ...")
+        ref_all = oracle_prefill(cfg, d)
+        err = float(np.abs(oracle.widen(got, cfg.dtype) - ref_all).max())
+        say("  prefill max abs err over every output row", err)
         assert err <= TOL[cfg.dtype]
+        # (the same rows once more by the other route: row i = decode with q_i over its visible keys)
+        assert sampled_rows_check(cfg, d, got) <= TOL[cfg.dtype]
         # grow every request by its new turn and write the rows
         cu = d["cu_seqlens"]
         new_total = (d["prefix_lens"] + d["new_lens"]).astype(np.int64)
@@ -221,9 +226,9 @@ def test_config4_multiturn_full_size_then_extend_and_decode(ctx):
         # rounding, and the same sampled rows against the oracle)
         again = run_prefill(ctx, cfg.dtype, d, reg.k_ptrs, reg.v_ptrs, cfg.n_kv_heads, cfg.scale, new_in_cache=True)
         assert np.isfinite(w(again)).all()
-        err2 = sampled_rows_check(cfg, d, again)
+        err2 = float(np.abs(w(again) - ref_all).max())
         diff = float(np.abs(w(again) - w(got)).max())
-        say("  in-cache prefill sampled rows max abs err", err2, "max abs difference to the first call", diff)
+        say("  in-cache prefill max abs err over every row", err2, "max abs difference to the first call", diff)
         assert err2 <= TOL[cfg.dtype] and diff <= TOL[cfg.dtype] / 2
     finally:
         reg.release()
@@ -252,6 +257,41 @@ def test_scores_far_above_the_first_keys(ctx, dtype, boost, where):
     assert np.abs(rows - np.repeat(want, G, axis=0)[None]).max() <= TOL[dtype]
 
 
+@pytest.mark.parametrize("scale", [-0.2, 0.0, 1.5])
+def test_any_finite_scale(ctx, scale):
+    """Negative (the smallest score weighs most), zero (plain mean of the visible value rows) and large scales follow
+    the same definition."""
+    cfg = CONFIGS[3].replace(batch=3, kv_len=(0, 500), new_len=(1, 200))
+    check_prefill(ctx, cfg, workloads.prefill_inputs(cfg, seed=52), "scale %g" % scale, scale=scale)
+    cfg = cfg.replace(dtype="f16", head_dim=64, n_q_heads=6, n_kv_heads=2)
+    check_prefill(ctx, cfg, workloads.prefill_inputs(cfg, seed=53), "scale %g f16" % scale, new_in_cache=True, scale=scale)
+
+
+@pytest.mark.parametrize("gap,where", [(15.0, 0), (18.0, 17), (21.5, 31), (21.5, 3), (24.0, 9), (30.0, 30)])
+def test_fp16_outlier_among_the_first_keys_of_a_long_prefix(ctx, gap, where):
+    """fp16 weights have a short exponent range.  One of the first 32 cached keys scores `gap` log2 units above all
+    the others, which all score 0, and there are 20000 of them with value rows of ones against the outlier's zeros:
+    the output is w / (1 + w) in every coordinate with w = 20000 * 2^-gap, and a kernel that fixes its reference
+    maximum on the first keys must not flush the small weights to zero (w = 0.007 at gap 21.5 is above the tolerance)."""
+    P, N, dtype = 20000, 70, "f16"
+    cfg, d = with_lens(CONFIGS[3].replace(dtype=dtype, n_q_heads=4, n_kv_heads=1), [P], [N], seed=88)
+    f16 = lambda x: np.asarray(x, np.float16).view(np.uint16)
+    d["q_new"][:] = f16(0.5)
+    d["k"][0][:] = f16(0.0)
+    d["k_new"][:] = f16(0.0)
+    d["v"][0][:] = f16(1.0)
+    d["v_new"][:] = f16(1.0)
+    c = gap / (1.4426950408889634 * 64.0 * cfg.scale)             # score = c * sum(q) * scale, in log2 units: gap
+    d["k"][0][where] = f16(c)
+    d["v"][0][where] = f16(0.0)
+    got = check_prefill(ctx, cfg, d, "fp16-outlier gap %g at %d" % (gap, where))
+    c_exact = float(np.float16(c))
+    i = np.arange(N)
+    w = (P - 1 + i + 1) * np.exp(-c_exact * 64.0 * 0.5 * cfg.scale)
+    want = (w / (1.0 + w))[:, None, None]
+    assert np.abs(oracle.widen(got, dtype) - want).max() <= TOL[dtype]
+
+
 def test_bad_arguments_are_refused(ctx):
     t = torch.zeros(4, 8, 128, dtype=torch.int16).cuda()
     cu, pl = np.array([0, 4], np.int32), np.array([3], np.int32)
@@ -261,8 +301,8 @@ def test_bad_arguments_are_refused(ctx):
     for change, status in ((dict(v_new=None), vt.VT_E_INVALID), (dict(head_dim=80), vt.VT_E_UNSUPPORTED),
                            (dict(total_new_tokens=5), vt.VT_E_INVALID), (dict(n_kv_heads=5), vt.VT_E_INVALID),
                            (dict(prefix_lens_host=np.array([-1], np.int32)), vt.VT_E_INVALID),
-                           (dict(out=None), vt.VT_E_INVALID), (dict(scale=0.0), vt.VT_E_INVALID),
-                           (dict(scale=-1.0), vt.VT_E_INVALID)):
+                           (dict(out=None), vt.VT_E_INVALID), (dict(scale=float("nan")), vt.VT_E_INVALID),
+                           (dict(scale=float("-inf")), vt.VT_E_INVALID)):
         with pytest.raises(vt.VtError) as e:
             vt.vt_attn_prefix_prefill(ctx, vt.make_prefill_args(**dict(ok, **change)), stream())
         assert e.value.status == status, change
