@@ -42,7 +42,8 @@ typedef enum {
   VT_E_CAPACITY = -2,    /* length beyond the region's max_tokens                                     */
   VT_E_OOM = -3,         /* physical budget (max_phys_bytes) or device memory exhausted               */
   VT_E_DRIVER = -4,      /* a HIP call failed                                                         */
-  VT_E_UNSUPPORTED = -5  /* (dtype, head_dim, group size) combination without a kernel                */
+  VT_E_UNSUPPORTED = -5, /* (dtype, head_dim, group size) combination without a kernel                */
+  VT_E_WORKSPACE = -6    /* vt_attn_decode_static: the call needs more than the fixed scratch buffer  */
 } vt_status;
 
 typedef struct {
@@ -190,6 +191,21 @@ int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batc
  * Errors: VT_E_INVALID for null pointers, n_q_heads % n_kv_heads != 0 or a host length < 1;
  * VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 256 and batch <= 4096. */
 int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* args, void* stream);
+
+/* vt_attn_decode for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bits as vt_attn_decode, but the
+ * tape table and the pieces' partial results live in a fixed device array that is part of the loaded library
+ * (vt_static_scratch_bytes() bytes, 32 MiB, held by every GPU the library runs on until the process ends) instead
+ * of the context's workspace.  The call allocates and frees nothing, on the host's device heap or through any
+ * library, records no events (vt_profile_enable does not cover it) and only enqueues its two kernels on `stream`.
+ * A call whose plan needs more (vt_plan_decode's workspace_bytes > vt_static_scratch_bytes(); e.g. batch 256
+ * with 64 query heads cut three ways fits, batch 4096 with 64 query heads does not) returns VT_E_WORKSPACE and
+ * launches nothing.  Nothing in the buffer has to start at zero: the merge reads only what the split pass of the
+ * same call wrote.  All calls on one GPU share the one buffer, from every context and stream: two calls that
+ * overlap in time on one GPU race on it; calls on one stream, or otherwise ordered, are safe.  Other errors as
+ * vt_attn_decode; VT_E_DRIVER if the buffer's address could not be looked up when the context was created. */
+int vt_attn_decode_static(vt_ctx* ctx, const vt_decode_args* args, void* stream);
+uint64_t vt_static_scratch_bytes(void);
 
 typedef struct {
   int32_t dtype;

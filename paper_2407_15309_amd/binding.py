@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvt.so")
 
 VT_F16, VT_BF16 = 1, 2
-VT_OK, VT_E_INVALID, VT_E_CAPACITY, VT_E_OOM, VT_E_DRIVER, VT_E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+VT_OK, VT_E_INVALID, VT_E_CAPACITY, VT_E_OOM, VT_E_DRIVER, VT_E_UNSUPPORTED, VT_E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
 DTYPES = {"f16": VT_F16, "bf16": VT_BF16}
 
 if not os.path.exists(LIB_PATH):
@@ -97,6 +97,7 @@ _SIGS = {
     "vt_plan_decode": [_vp, _vp, _u32, _u32, _u32, _u32, C.POINTER(Plan), _vp],
     "vt_plan_prefill": [_vp, _vp, _vp, _u32, _u32, _u32, _u32, C.c_int, C.POINTER(PrefillPlan), _vp, C.c_uint64, _vp],
     "vt_attn_decode": [_vp, C.POINTER(DecodeArgs), _vp],
+    "vt_attn_decode_static": [_vp, C.POINTER(DecodeArgs), _vp],
     "vt_attn_prefix_prefill": [_vp, C.POINTER(PrefillArgs), _vp],
     "vt_workspace_reserve": [_vp, _u64],
     "vt_set_plan_target": [_vp, _u64],
@@ -104,10 +105,12 @@ _SIGS = {
     "vt_profile_enable": [_vp, _i32],
     "vt_profile_collect": [_vp, _i32, C.POINTER(C.c_double), C.POINTER(_u64)],
 }
-EXPORTS = sorted(list(_SIGS) + ["vt_strerror"])
+EXPORTS = sorted(list(_SIGS) + ["vt_strerror", "vt_static_scratch_bytes"])
 for _n, _a in _SIGS.items():
     getattr(lib, _n).argtypes = _a
     getattr(lib, _n).restype = C.c_int
+lib.vt_static_scratch_bytes.argtypes = []
+lib.vt_static_scratch_bytes.restype = C.c_uint64
 lib.vt_strerror.argtypes = [C.c_int]
 lib.vt_strerror.restype = C.c_char_p
 
@@ -256,6 +259,14 @@ def make_decode_args(dtype: int, batch: int, n_q_heads: int, n_kv_heads: int, he
 
 def vt_attn_decode(ctx: int, args: DecodeArgs, stream: int = 0) -> None:
     _check(lib.vt_attn_decode(ctx, C.byref(args), stream), "vt_attn_decode")
+
+
+def vt_attn_decode_static(ctx: int, args: DecodeArgs, stream: int = 0) -> None:
+    _check(lib.vt_attn_decode_static(ctx, C.byref(args), stream), "vt_attn_decode_static")
+
+
+def vt_static_scratch_bytes() -> int:
+    return int(lib.vt_static_scratch_bytes())
 
 
 def make_prefill_args(dtype: int, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, scale: float,

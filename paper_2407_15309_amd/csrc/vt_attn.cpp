@@ -155,7 +155,8 @@ int vt_workspace_reserve(vt_ctx* ctx, uint64_t bytes) {
   return ensure_workspace(ctx, bytes);
 }
 
-int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
+// Argument checks and the integer plan shared by the two decode entry points.  VT_OK with batch 0 means "nothing to do".
+static int check_and_plan_decode(vt_ctx* ctx, const vt_decode_args* a, DecodePlan* plan) {
   if (!ok_ctx(ctx) || !a) return VT_E_INVALID;
   if (ctx->be->is_host()) return VT_E_UNSUPPORTED;
   if (a->batch == 0) return VT_OK;
@@ -164,14 +165,31 @@ int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
   if (a->dtype != VT_F16 && a->dtype != VT_BF16) return VT_E_INVALID;
   if (!std::isfinite(a->scale)) return VT_E_INVALID;
   if (!supported_dim(a->head_dim) || a->n_q_heads / a->n_kv_heads > 256) return VT_E_UNSUPPORTED;
+  if (a->batch > (uint32_t)kMaxDecodeBatch) return VT_E_UNSUPPORTED;
+  return plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, plan,
+                     nullptr);
+}
+
+int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
   DecodePlan plan;
-  int rc = plan_decode(ctx->plan_target, a->kv_lens_host, a->batch, a->n_kv_heads, a->n_q_heads, a->head_dim, &plan,
-                       nullptr);
-  if (rc != VT_OK) return rc;
+  int rc = check_and_plan_decode(ctx, a, &plan);
+  if (rc != VT_OK || a->batch == 0) return rc;
   rc = ensure_workspace(ctx, plan.ws_bytes);
   if (rc != VT_OK) return rc;
-  return launch_decode(ctx, a, plan, stream);
+  return launch_decode(ctx, a, plan, stream, ctx->ws, true);
 }
+
+int vt_attn_decode_static(vt_ctx* ctx, const vt_decode_args* a, void* stream) {
+  DecodePlan plan;
+  int rc = check_and_plan_decode(ctx, a, &plan);
+  if (rc != VT_OK || a->batch == 0) return rc;
+  if (plan.ws_bytes > kStaticScratchBytes) return VT_E_WORKSPACE;
+  void* ws = static_scratch_ptr(ctx->device);
+  if (!ws) return VT_E_DRIVER;  // the look-up at vt_init failed
+  return launch_decode(ctx, a, plan, stream, ws, false);
+}
+
+uint64_t vt_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   if (!ok_ctx(ctx) || !a) return VT_E_INVALID;

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "vt_internal.h"
 
@@ -440,20 +441,50 @@ __global__ void append_batch_kernel(char* const* k_ptrs, char* const* v_ptrs, co
 
 constexpr uint64_t kTapeBytes = ((uint64_t)(kMaxDecodeBatch + 1) * sizeof(int32_t) + 255) & ~255ull;
 
+// Scratch of vt_attn_decode_static: the same layout as the context workspace (tape table, then the pieces'
+// partial results), in device memory that belongs to the loaded code object, so the call allocates nothing.  Every
+// GPU the library runs on holds its own copy until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels get the looked-up device address as an argument.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];  // per device: address of its copy of `scratch` (null = not looked up yet)
+
 }  // namespace
+
+int static_scratch_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return VT_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (g_scratch_ptr[device]) return VT_OK;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+    (void)hipGetLastError();
+    return VT_E_DRIVER;
+  }
+  g_scratch_ptr[device] = ptr;
+  return VT_OK;
+}
+
+void* static_scratch_ptr(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  return g_scratch_ptr[device];
+}
 
 uint64_t decode_workspace_bytes(uint32_t batch, uint32_t max_pieces, uint32_t hq, uint32_t d) {
   return kTapeBytes + (uint64_t)batch * max_pieces * hq * (d + 2) * sizeof(float);
 }
 
-int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream) {
+int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream, void* workspace,
+                  bool allow_profile) {
   if (a->batch > (uint32_t)kMaxDecodeBatch) return VT_E_UNSUPPORTED;
   DecodeParams p;
   p.q = (const char*)a->q;
   p.k_ptrs = (const char* const*)a->k_ptrs;
   p.v_ptrs = (const char* const*)a->v_ptrs;
   p.kv_lens = a->kv_lens;
-  char* ws = (char*)ctx->ws;
+  char* ws = (char*)workspace;
   p.tape = (int32_t*)ws;
   const size_t n_part = (size_t)a->batch * plan.max_pieces * a->n_q_heads;
   p.part_acc = (float*)(ws + kTapeBytes);
@@ -474,11 +505,11 @@ int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, 
   const uint32_t blocks = (uint32_t)((waves + kWaves - 1) / kWaves);
   const dim3 cgrid(p.hq, a->batch);
   const bool combine = plan.max_pieces > 1;
-  prof_begin(ctx, 0, st);
+  if (allow_profile) prof_begin(ctx, 0, st);
 #define VT_LAUNCH(DT, DD)                                                                        \
   do {                                                                                           \
     hipLaunchKernelGGL((decode_kernel<DT, DD>), dim3(blocks), dim3(64 * kWaves), 0, st, p);      \
-    prof_end(ctx, st);                                                                           \
+    if (allow_profile) prof_end(ctx, st);                                                        \
     if (combine) hipLaunchKernelGGL((decode_combine_kernel<DT, DD>), cgrid, dim3(DD), 0, st, p); \
   } while (0)
   if (a->dtype == VT_BF16 && a->head_dim == 128)

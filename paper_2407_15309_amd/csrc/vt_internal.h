@@ -112,6 +112,13 @@ int plan_decode(uint64_t target, const int32_t* lens, uint32_t batch, uint32_t h
 // Bytes of device workspace a decode launch needs: the tape prefix sums and the partial results.
 uint64_t decode_workspace_bytes(uint32_t batch, uint32_t max_pieces, uint32_t hq, uint32_t d);
 
+// Fixed scratch of the entry point that allocates nothing (the array lives in vt_decode.hip).  static_scratch_init
+// looks up the current device's copy once (call with `device` current); static_scratch_ptr returns it, null if the
+// look-up has not run or failed.
+constexpr uint64_t kStaticScratchBytes = 32ull << 20;
+int static_scratch_init(int device);
+void* static_scratch_ptr(int device);
+
 // Grows the context's device workspace to at least `bytes`.
 int ensure_workspace(vt_ctx* ctx, uint64_t bytes);
 
@@ -120,7 +127,9 @@ void prof_begin(vt_ctx* ctx, int which, void* stream);
 void prof_end(vt_ctx* ctx, void* stream);
 
 // Kernel launchers (device code lives in the .hip files).
-int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream);
+// `workspace`: device memory of at least plan.ws_bytes bytes.
+int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, void* stream, void* workspace,
+                  bool allow_profile);
 int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream);
 int plan_prefill(const vt_ctx* ctx, const int32_t* cu_host, const int32_t* plens_host, uint32_t batch, uint32_t hq,
                  uint32_t hkv, uint32_t d, bool split, vt_prefill_plan* out, vt_prefill_piece* pieces,

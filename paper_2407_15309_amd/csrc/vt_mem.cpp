@@ -457,6 +457,9 @@ int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_by
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
     (*out)->n_cus = cus;
+  // Address of this device's copy of the fixed scratch (the device is current).  A failure only disables
+  // vt_attn_decode_static, which then reports VT_E_DRIVER.
+  (void)static_scratch_init(device);
   return VT_OK;
 }
 
@@ -707,6 +710,7 @@ const char* vt_strerror(int status) {
     case VT_E_OOM: return "out of physical memory budget";
     case VT_E_DRIVER: return "HIP driver call failed";
     case VT_E_UNSUPPORTED: return "unsupported configuration";
+    case VT_E_WORKSPACE: return "the call needs more scratch memory than the fixed buffer holds";
     default: return "unknown status";
   }
 }
