@@ -152,7 +152,7 @@ def prefill_plan(cu_seqlens: Sequence[int], prefix_lens: Sequence[int], n_q_head
             pieces.append(tuple(run))
         begin += cost(tiles)
     piece_floats = 512 + 256 * head_dim
-    ws = 2 * n_groups * piece_floats * 4 + n_groups * 32
+    ws = 2 * n_groups * piece_floats * 4
     # pieces are executed group by group; within a group in item order (which is the order built above)
     pieces.sort(key=lambda p: p[0])
     return total, n_tiles, len(items), n_groups, ws, pieces

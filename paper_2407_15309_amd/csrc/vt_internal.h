@@ -77,6 +77,9 @@ struct vt_ctx {
   vt_stats_t st;
   void* ws;
   uint64_t ws_bytes;
+  void* arrivals;             // device, kMaxPrefillGroups 8-byte words, zero at creation: arrival counts of the
+                              // prefix-prefill items shared between workgroups, tagged with the launch number
+  uint64_t prefill_launches;  // prefix-prefill launches on this context so far
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;
@@ -98,6 +101,7 @@ namespace vt {
 inline bool ok_ctx(const vt_ctx* c) { return c && c->magic == VT_CTX_MAGIC; }
 inline bool ok_kv(const vt_kv* k) { return k && k->magic == VT_KV_MAGIC && k->alive && ok_ctx(k->ctx); }
 
+constexpr int kMaxPrefillGroups = 1024;  // workgroups of a prefix-prefill launch (one per compute unit at most)
 constexpr int kMaxPrefillBatch = 1024;  // requests per prefix-prefill launch (the item order lives in LDS)
 constexpr int kMaxDecodeBatch = 4096;  // requests per decode launch (the tape prefix table lives in LDS)
 

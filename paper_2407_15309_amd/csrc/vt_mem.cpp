@@ -203,6 +203,8 @@ int make_ctx(vt_ctx** out, Backend* be, int device, uint64_t chunk_bytes, uint64
   std::memset(&c->st, 0, sizeof(c->st));
   c->ws = nullptr;
   c->ws_bytes = 0;
+  c->arrivals = nullptr;
+  c->prefill_launches = 0;
   c->n_cus = 256;
   c->profile = false;
   *out = c;
@@ -457,6 +459,17 @@ int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_by
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
     (*out)->n_cus = cus;
+  if ((*out)->n_cus > kMaxPrefillGroups) (*out)->n_cus = kMaxPrefillGroups;
+  void* arr = nullptr;
+  if (hipMalloc(&arr, (size_t)kMaxPrefillGroups * 8) != hipSuccess ||
+      hipMemset(arr, 0, (size_t)kMaxPrefillGroups * 8) != hipSuccess) {
+    (void)hipGetLastError();
+    if (arr) (void)hipFree(arr);
+    vt_destroy(*out);
+    *out = nullptr;
+    return VT_E_OOM;
+  }
+  (*out)->arrivals = arr;
   // Address of this device's copy of the fixed scratch (the device is current).  A failure only disables
   // vt_attn_decode_static, which then reports VT_E_DRIVER.
   (void)static_scratch_init(device);
@@ -506,6 +519,8 @@ int vt_destroy(vt_ctx* ctx) {
     ctx->prof.clear();
     if (ctx->ws) (void)hipFree(ctx->ws);
     ctx->ws = nullptr;
+    if (ctx->arrivals) (void)hipFree(ctx->arrivals);
+    ctx->arrivals = nullptr;
     delete ctx->be;
     ctx->be = nullptr;
     ctx->magic = 0;

@@ -118,7 +118,9 @@ struct PrefillParams {
   float scale_log2e;                   // |scale| * log2(e), at least the smallest normal number
   uint32_t q_sign;                     // 0x80008000 when scale < 0 (the query values are negated instead), else 0
   uint32_t total_cost, n_groups;       // cost units of the whole call, workgroups sharing them
-  float* ws;                           // 2 * n_groups piece slots, then n_groups shared-item records
+  float* ws;                           // 2 * n_groups piece slots
+  unsigned long long* arrivals;        // one word per group: (launch number << 16) | pieces of its shared item done
+  unsigned long long launch;           // number of this launch on the context, from 1
 };
 
 // Key tiles of item (request with P cached and N new tokens, token tile t of tb tokens).  The keys it sees
@@ -165,13 +167,6 @@ __host__ __device__ inline uint32_t group_begin(uint32_t total, uint32_t n, uint
 }
 // Floats of one piece slot: 256 maxima, 256 sums, 256 x D accumulators.
 __host__ __device__ constexpr uint32_t piece_floats(int d) { return 512u + 256u * (uint32_t)d; }
-// Record of an item that starts in a workgroup's range and ends in a later one (written by the main kernel,
-// read by the merge kernel).
-struct SharedItem {
-  uint32_t valid, cost_begin;  // first cost unit of the item in the whole sequence
-  int32_t b, g, t, nkt, nfast, pad;
-};
-
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr uniform).
 // Written as assembly so that these loads are invisible to the compiler's wait-count bookkeeping: it would
 // otherwise guard operand reads of the tile buffers with waits for every outstanding load.  The kernel places
@@ -182,6 +177,16 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint3
                :
                : "v"(lane_off), "s"(base), "s"(lds_addr)
                : "memory");
+}
+// Accesses at device scope for data that workgroups on different XCDs hand to each other inside one launch (each
+// XCD has its own L2): the store goes through to memory, the load does not take the line from this XCD's L2.
+// Written as assembly so that they come 16 bytes wide; the caller waits (wait_device_accesses) before it relies on a
+// store having landed or uses a loaded value.
+__device__ __forceinline__ void store16_device(float* p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void load16_device(f32x4& v, const float* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
 }
 // Marks a value that is the same in every lane as such (it then lives in scalar registers).
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -258,6 +263,25 @@ __device__ __forceinline__ void build_prefix(const PrefillParams& p, uint32_t* s
   __syncthreads();
 }
 
+// One contiguous run of an item's tiles, computed by this workgroup.  Every field is the same in all lanes.
+struct Tile {
+  const char* k;
+  const char* v;
+  int last_row;  // rows 0 .. last_row exist
+  int jbase;     // absolute position of the key in row 0
+};
+struct Piece {
+  int valid;
+  int b, g, t;            // the item: request, kv head, token tile
+  int P, N, cu_b;         // cached rows, new rows, first new row of the request
+  int s0, s1;             // tiles [s0, s1) of the item's sweep
+  int nkt, nfast;         // tiles and fast tiles of the whole item
+  uint32_t item_begin;    // first cost unit of the item in the whole sequence
+  uint32_t end_pos;       // cost unit after the piece: the end of its item, or the end of the workgroup's range
+  int lenA, lenB, nA, fastA, fastB;
+  const char *kc, *vc, *kn, *vn;  // row 0 of segment A (region) and of segment B (k_new / v_new), at this kv head
+};
+
 template <int DT, int D>
 __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int CH = D / 8;            // 16-byte chunks per head row
@@ -268,11 +292,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
   constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
+  constexpr int STG = 64 + 16;         // bytes of one output staging row: 32 values and a pad
   // Four tile buffers (K tile, then V tile), separate arrays rather than one array indexed by the buffer number.
   __shared__ __attribute__((aligned(1024))) char lds_t0[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t1[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t2[2 * TILEB];
   __shared__ __attribute__((aligned(1024))) char lds_t3[2 * TILEB];
+  // Output staging, one area per wavefront (the tile buffers are never free: the next piece's tiles are on their way).
+  __shared__ __attribute__((aligned(16))) char lds_stage[4][64 * STG];
   __shared__ uint32_t s_pre[kMaxPrefillBatch + 1];
   // Lengths and region addresses of the first few requests this workgroup works on, fetched once: a piece then
   // starts without a round trip to memory for them.
@@ -280,6 +307,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   __shared__ int s_wP[kWin], s_wN[kWin], s_wCu[kWin];
   __shared__ const char* s_wK[kWin];
   __shared__ const char* s_wV[kWin];
+  // Per wavefront: the three tiles that follow the current piece in this workgroup's tile stream (address of K row
+  // 0, of V row 0, last row), written when the piece starts and read when the loads run past its end.
+  __shared__ int s_ahead[4][3][6];
+  __shared__ int s_vote[4];
+  __shared__ unsigned s_arrived;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -295,8 +327,6 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const uint32_t group = xcd_run_index(blockIdx.x, p.n_groups);
   uint32_t cursor = group_begin(p.total_cost, p.n_groups, group);
   const uint32_t range_end = group_begin(p.total_cost, p.n_groups, group + 1);
-  SharedItem* shared_items = (SharedItem*)(p.ws + (size_t)2 * p.n_groups * piece_floats(D));
-  SharedItem my_shared = {};
   const int b_win = cursor < range_end ? find_request(p, s_pre, cursor) : 0;
   if (tid < kWin && b_win + tid < (int)p.batch) {
     const int r = b_win + tid;
@@ -308,101 +338,212 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   }
   __syncthreads();
 
-  for (; cursor < range_end;) {
-  // ---- the piece: tiles s0 .. s1-1 of item (b, g, t): those whose first cost unit lies in this range ----
-  const int b = find_request(p, s_pre, cursor);
-  const bool in_win = b - b_win < kWin;
-  const int wi = in_win ? b - b_win : 0;
-  const int cu_b = uni(in_win ? s_wCu[wi] : p.cu[b]), P = uni(in_win ? s_wP[wi] : p.plens[b]);
-  const int N = uni(in_win ? s_wN[wi] : p.cu[b + 1] - p.cu[b]);
-  const ItemPos pos = locate(p, s_pre, cursor, split_src, b, P, N);
-  const uint32_t c1 = min(item_cost(pos.shape), pos.c + (range_end - cursor));
-  const int g = pos.g;
-  const int s0 = tile_at(pos.shape, pos.c), s1 = tile_at(pos.shape, c1);
-  const uint32_t piece_cursor = cursor;
-  cursor += c1 - pos.c;
-  if (s1 <= s0) continue;
-  const bool whole = s0 == 0 && s1 == pos.shape.nkt;
-  // A piece that continues an item goes to slot 2w, the first piece of an item that ends in a later range to slot
-  // 2w+1 (a workgroup has at most one of each).
-  const uint32_t slot = 2 * group + (s0 > 0 ? 0u : 1u);
-  if (!whole && s0 == 0) {
-    my_shared.valid = 1;
-    my_shared.cost_begin = piece_cursor - pos.c;
-    my_shared.b = b;
-    my_shared.g = g;
-    my_shared.t = pos.t;
-    my_shared.nkt = pos.shape.nkt;
-    my_shared.nfast = pos.shape.nfast;
-  }
-  const int tok0 = pos.t * tb;
-  const int ntok = min(tb, N - tok0);
-  const int vis = tok0 + ntok;                 // new rows the last token of the tile sees
-  // Two key segments: A = rows of the region (the cached prefix; also the new rows when they are already in the
-  // cache), B = rows of k_new / v_new.  Each is tiled from its own row 0.
-  const int lenA = split_src ? P : P + vis, lenB = split_src ? vis : 0;
-  const int nA = (lenA + kBN - 1) / kBN;
-  // Tiles whose 64 keys every row of the workgroup sees: inside a segment and not beyond the first token.
-  const int fastA = min(lenA, P + tok0 + 1) / kBN;
-  const int fastB = split_src ? (tok0 + 1) / kBN : 0;
-  const int nfast_item = fastA + fastB;
-  const char* kc = uni(in_win ? s_wK[wi] : p.k_ptrs[b]) + (size_t)g * ROWB;
-  const char* vc = uni(in_win ? s_wV[wi] : p.v_ptrs[b]) + (size_t)g * ROWB;
-  const char* kn = split_src ? uni(p.k_new + (size_t)cu_b * row_bytes + (size_t)g * ROWB) : kc;
-  const char* vn = split_src ? uni(p.v_new + (size_t)cu_b * row_bytes + (size_t)g * ROWB) : vc;
-  // The item's tiles are swept in this order: the fast tiles of A, the fast tiles of B, then the rest of A (its
-  // ragged last tile) and the rest of B (the causal diagonal).  Softmax does not care about the order of the
-  // keys, and this way the unmasked tiles come first.  Tile s of the sweep:
-  struct Tile {
-    const char* k;
-    const char* v;
-    int last_row;  // rows 0 .. last_row exist
-    int jbase;     // absolute position of the key in row 0
+  // Fills in the fields of a piece that follow from its item (b, g, t), the request's lengths and its tile range.
+  auto finish_piece = [&](Piece& r, const char* k_req, const char* v_req) {
+    const int tok0 = r.t * tb;
+    const int vis = min(tok0 + tb, r.N);          // new rows the last token of the tile sees
+    // Two key segments: A = rows of the region (the cached prefix; also the new rows when they are already in
+    // the cache), B = rows of k_new / v_new.  Each is tiled from its own row 0.
+    r.lenA = split_src ? r.P : r.P + vis;
+    r.lenB = split_src ? vis : 0;
+    r.nA = (r.lenA + kBN - 1) / kBN;
+    // Tiles whose 64 keys every row of the workgroup sees: inside a segment and not beyond the first token.
+    r.fastA = min(r.lenA, r.P + tok0 + 1) / kBN;
+    r.fastB = split_src ? (tok0 + 1) / kBN : 0;
+    r.kc = k_req + (size_t)r.g * ROWB;
+    r.vc = v_req + (size_t)r.g * ROWB;
+    r.kn = split_src ? uni(p.k_new + (size_t)r.cu_b * row_bytes + (size_t)r.g * ROWB) : r.kc;
+    r.vn = split_src ? uni(p.v_new + (size_t)r.cu_b * row_bytes + (size_t)r.g * ROWB) : r.vc;
   };
-  auto tile_of = [&](int s) -> Tile {
+  // Lengths and region bases of request b (from the window when it is there).
+  struct Req {
+    int P, N, cu_b;
+    const char *k, *v;
+  };
+  auto request = [&](int b) -> Req {
+    const bool in_win = b - b_win < kWin;
+    const int wi = in_win ? b - b_win : 0;
+    Req q;
+    q.cu_b = uni(in_win ? s_wCu[wi] : p.cu[b]);
+    q.P = uni(in_win ? s_wP[wi] : p.plens[b]);
+    q.N = uni(in_win ? s_wN[wi] : p.cu[b + 1] - p.cu[b]);
+    q.k = uni(in_win ? s_wK[wi] : p.k_ptrs[b]);
+    q.v = uni(in_win ? s_wV[wi] : p.v_ptrs[b]);
+    return q;
+  };
+  // The first piece of this workgroup's range: the tiles of an item whose first cost unit lies in the range
+  // (valid = 0 when the range holds none).  A search in the table of request costs; later pieces follow from
+  // their predecessor (next_piece).
+  auto first_piece = [&](uint32_t pos) -> Piece {
+    Piece r;
+    r.valid = 0;
+    while (pos < range_end) {
+      const int b = find_request(p, s_pre, pos);
+      const Req q = request(b);
+      const ItemPos ip = locate(p, s_pre, pos, split_src, b, q.P, q.N);
+      const uint32_t cost = item_cost(ip.shape);
+      const uint32_t c1 = min(cost, ip.c + (range_end - pos));
+      const int s0 = tile_at(ip.shape, ip.c), s1 = tile_at(ip.shape, c1);
+      const uint32_t item_begin = pos - ip.c;
+      pos += c1 - ip.c;
+      if (s1 <= s0) continue;
+      r.valid = 1;
+      r.b = b;
+      r.g = ip.g;
+      r.t = ip.t;
+      r.P = q.P;
+      r.N = q.N;
+      r.cu_b = q.cu_b;
+      r.s0 = s0;
+      r.s1 = s1;
+      r.nkt = ip.shape.nkt;
+      r.nfast = ip.shape.nfast;
+      r.item_begin = item_begin;
+      r.end_pos = pos;
+      finish_piece(r, q.k, q.v);
+      return r;
+    }
+    return r;
+  };
+  // The piece after `pc` in this workgroup's range.  When pc stops at the end of the range there is none; otherwise
+  // pc ran to the end of its item and the next item starts where it ended: the next token tile of the same request
+  // and kv head, else the next kv head, else the next request that has new tokens.
+  auto next_piece = [&](const Piece& pc) -> Piece {
+    Piece r = pc;
+    r.valid = 0;
+    if (pc.end_pos >= range_end) return r;
+    const char* k_req = pc.kc - (size_t)pc.g * ROWB;
+    const char* v_req = pc.vc - (size_t)pc.g * ROWB;
+    r.t = pc.t + 1;
+    if (r.t * tb >= pc.N) {
+      r.t = 0;
+      r.g = pc.g + 1;
+      if (r.g == (int)p.hkv) {
+        r.g = 0;
+        Req q;
+        q.N = 0;
+        int b = pc.b;
+        while (q.N == 0) {
+          if (++b >= (int)p.batch) return r;  // (cannot happen: the range ends with the last item)
+          q = request(b);
+        }
+        r.b = b;
+        r.P = q.P;
+        r.N = q.N;
+        r.cu_b = q.cu_b;
+        k_req = q.k;
+        v_req = q.v;
+      }
+    }
+    const ItemShape sh = item_shape(r.P, r.N, r.t, tb, split_src);
+    const uint32_t c1 = min(item_cost(sh), range_end - pc.end_pos);
+    r.item_begin = pc.end_pos;
+    r.end_pos = pc.end_pos + c1;
+    r.s0 = 0;
+    r.s1 = tile_at(sh, c1);
+    r.nkt = sh.nkt;
+    r.nfast = sh.nfast;
+    if (r.s1 <= 0) return r;  // the range ends before the item's first tile
+    r.valid = 1;
+    finish_piece(r, k_req, v_req);
+    return r;
+  };
+  // An item's tiles are swept in this order: the fast tiles of A, the fast tiles of B, then the rest of A (its
+  // ragged last tile) and the rest of B (the causal diagonal).  Softmax does not care about the order of the
+  // keys, and this way the unmasked tiles come first.  Tile s of the sweep of piece pc's item:
+  auto tile_in = [&](const Piece& pc, int s) -> Tile {
     // (bitwise operators on purpose: plain scalar selects, no branches in the middle of the tile code)
-    const bool in_b = ((s >= fastA) & (s < nfast_item)) | (s >= nfast_item + nA - fastA);
-    const int tt = s - (s < fastA ? 0 : (s < nfast_item ? fastA : (in_b ? nA : fastB)));
+    const int nfast_item = pc.fastA + pc.fastB;
+    const bool in_b = ((s >= pc.fastA) & (s < nfast_item)) | (s >= nfast_item + pc.nA - pc.fastA);
+    const int tt = s - (s < pc.fastA ? 0 : (s < nfast_item ? pc.fastA : (in_b ? pc.nA : pc.fastB)));
     Tile r;
     const size_t off = (size_t)tt * kBN * row_bytes;
-    r.k = (in_b ? kn : kc) + off;
-    r.v = (in_b ? vn : vc) + off;
-    r.last_row = min(kBN, (in_b ? lenB : lenA) - tt * kBN) - 1;
-    r.jbase = (in_b ? P : 0) + tt * kBN;
+    r.k = (in_b ? pc.kn : pc.kc) + off;
+    r.v = (in_b ? pc.vn : pc.vc) + off;
+    r.last_row = min(kBN, (in_b ? pc.lenB : pc.lenA) - tt * kBN) - 1;
+    r.jbase = (in_b ? pc.P : 0) + tt * kBN;
     return r;
   };
 
-  // Descriptor for a tile that is loaded ahead of its use.  Past the end of the piece the loads go on (so that the
-  // count of outstanding loads, and with it the wait at every tile, stays the same), into buffers nobody reads:
-  // every lane then fetches from row 0 of the last tile - a few cache lines instead of a tile.
+  // The piece being computed.  (Plain variables rather than the struct in the lambdas below: the tile code refers
+  // to a handful of them only.)
+  Piece cur = first_piece(cursor);
+  if (!cur.valid) return;
+  int s0, s1, P, ntok;
+  auto tile_of = [&](int s) -> Tile { return tile_in(cur, s); };
+  // Descriptor for a tile that is loaded ahead of its use.  The workgroup's pieces form one stream of tiles and the
+  // loads run three tiles ahead of the arithmetic right through the piece boundaries: past the end of the piece
+  // they fetch the first tiles of the next pieces (looked up once per piece and parked in LDS, see park_ahead).
+  // Past the end of the stream the loads go on as well (so that the count of outstanding loads, and with it the
+  // wait at every tile, stays the same), into buffers nobody reads: every lane then fetches from row 0 of the last
+  // tile - a few cache lines instead of a tile.
   auto tile_ahead = [&](int s) -> Tile {
-    Tile r = tile_of(min(s, s1 - 1));
-    r.last_row = s < s1 ? r.last_row : 0;
+    if (__builtin_expect(s < s1, 1)) return tile_of(s);
+    asm volatile("" ::: "memory");  // a real branch: the look-up is not to be hoisted above the test
+    const int* a = s_ahead[wave][s - s1];
+    Tile r;
+    const uint32_t klo = (uint32_t)uni(a[0]), khi = (uint32_t)uni(a[1]);
+    const uint32_t vlo = (uint32_t)uni(a[2]), vhi = (uint32_t)uni(a[3]);
+    r.k = (const char*)(((uint64_t)khi << 32) | klo);
+    r.v = (const char*)(((uint64_t)vhi << 32) | vlo);
+    r.last_row = uni(a[4]);
+    r.jbase = 0;
     return r;
   };
+  // Looks up the three tiles that follow the current piece in the stream and parks them.
+  auto park_ahead = [&]() {
+    Piece nx = next_piece(cur);
+    int s = 0;
+    Tile last = tile_of(s1 - 1);
+    last.last_row = 0;
+#pragma unroll 1
+    for (int j = 0; j < 3; ++j) {
+      if (nx.valid && s >= nx.s1) {
+        nx = next_piece(nx);
+        s = 0;
+      }
+      Tile tl = last;
+      if (nx.valid) {
+        tl = tile_in(nx, s++);
+        last = tl;
+        last.last_row = 0;
+      }
+      int* a = s_ahead[wave][j];
+      a[0] = (int)(uint32_t)(uint64_t)tl.k;
+      a[1] = (int)(uint32_t)((uint64_t)tl.k >> 32);
+      a[2] = (int)(uint32_t)(uint64_t)tl.v;
+      a[3] = (int)(uint32_t)((uint64_t)tl.v >> 32);
+      a[4] = tl.last_row;
+    }
+  };
 
-  // Query rows of this lane (one per 32-column block) and their causal limits.
+  // Query rows of this lane (one per 32-column block): the G heads of the group for consecutive tokens.  Rows past
+  // the last token of the tile are padding: zeros (their scores and weights are then constants, the cheapest
+  // operands to multiply), never written.  A negative scale is applied as |scale| to scores of the negated queries:
+  // the kernel takes maxima of raw scores and multiplies afterwards, which needs a non-negative factor.
+  auto load_q = [&](const Piece& pc, u32x4 (*q)[KS]) {
+    const int tok0 = pc.t * tb, nt = min(tb, pc.N - tok0);
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const int r = wave * 64 + cb * 32 + col;
+      const int t = r / G, q_head = r - t * G;
+      const int q_tok = min(t, nt - 1);
+      const unsigned keep = t < nt ? 0xffffffffu : 0u;
+      const char* qp = p.q + ((size_t)(pc.cu_b + tok0 + q_tok) * p.hq + (size_t)pc.g * G + q_head) * ROWB;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 raw = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
+        q[cb][ks] = u32x4{(raw[0] ^ p.q_sign) & keep, (raw[1] ^ p.q_sign) & keep, (raw[2] ^ p.q_sign) & keep,
+                          (raw[3] ^ p.q_sign) & keep};
+      }
+    }
+  };
   int lim[2];
   u32x4 qf[2][KS];
-#pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
-    const int r = wave * 64 + cb * 32 + col;
-    const int t = r / G, q_head = r - t * G;
-    const int q_tok = min(t, ntok - 1);        // rows past the last token repeat it (and are not written)
-    lim[cb] = P + tok0 + q_tok;                // key j is visible iff j <= lim
-    const char* qp = p.q + ((size_t)(cu_b + tok0 + q_tok) * p.hq + (size_t)g * G + q_head) * ROWB;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      // (a negative scale is applied as |scale| to scores of the negated queries: the kernel takes maxima of raw
-      // scores and multiplies afterwards, which needs a non-negative factor)
-      const u32x4 raw = *(const u32x4*)(qp + (16 * ks + 8 * hi) * 2);
-      qf[cb][ks] = u32x4{raw[0] ^ p.q_sign, raw[1] ^ p.q_sign, raw[2] ^ p.q_sign, raw[3] ^ p.q_sign};
-    }
-  }
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
-  // Rows past the last token of the tile are padding; a wavefront whose 64 rows are all padding computes nothing.
-  const bool wave_idle = (wave * 64) / G >= ntok;
+  bool wave_idle;
+  load_q(cur, qf);
 
   // Tile loads.  Load i of this wavefront fills LDS rows (NLD*wave + i)*RPI .. +RPI-1 of the tile; the lane
   // lands in row `row` at chunk position ld_pos and therefore fetches the chunk that the swizzle assigns to
@@ -542,7 +683,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (NW & 15) | ((NW >> 4) << 14));
   };
   constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
-  // Tile pipeline.  Tile kt of the piece lives in buffer (kt - s0) % 4.  While tile kt is computed, tiles kt+1
+  // Tile pipeline.  The workgroup's tiles form one stream; the tile at stream position i lives in buffer i % 4.
+  // While tile kt is computed, tiles kt+1
   // and kt+2 are in flight or landed.  Every tile kt follows the same protocol.  Before its synchronisation
   // point it issues loads 1 and 2 of tile kt+2 (only load 1 when a tile has two loads per tensor).  At the
   // synchronisation point the wavefront waits until its own part of tile kt+1 has landed - loads complete in
@@ -714,232 +856,326 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
 
-  // Fast tiles of this piece: s0 .. nf-1.
-  int nf = min(s1, nfast_item);
-  for (int attempt = 0;; ++attempt) {
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) zero(acc[db][cb]);
-    m_used[0] = m_used[1] = -INFINITY;
-    l_run[0] = l_run[1] = 0.f;
+  // Workgroup barrier for data exchanged through LDS: waits for this wavefront's LDS operations only (the barrier
+  // of __syncthreads would wait for the tile loads in flight as well).
+  auto lds_barrier = []() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    issue_tile(tile_of(s0), lds_t0, lds_t0 + TILEB);
-    issue_tile(tile_ahead(s0 + 1), lds_t1, lds_t1 + TILEB);
-    Tile t2 = tile_ahead(s0 + 2);
-    issue_part(part0, t2, lds_t2, lds_t2 + TILEB);
-    wait_loads(std::integral_constant<int, VM + 2>{});
-    __builtin_amdgcn_s_barrier();
-    // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
-    // the vector registers to the scores, the weights and the in-flight LDS operand reads.  They are pinned
-    // there only now, so that their loads and the first tiles' loads are in flight together.
+  // acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row (cb*32 + col of the wavefront's 64).
+  // out[row, d] = acc * inv.  The rows go through LDS, 32 values of each at a time, so that the global stores are
+  // whole 16-byte pieces of 64 contiguous bytes per row rather than 8 bytes per lane scattered over 32 rows.
+  auto write_rows = [&](const Piece& pc, const float* inv) {
+    const int tok0 = pc.t * tb, nt = min(tb, pc.N - tok0);
+    char* stg = lds_stage[wave];
+    const unsigned g_magic = (65536u + (unsigned)G - 1u) / (unsigned)G;  // r / G for r < 256
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int db = 0; db < DB; ++db) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
-    int kt = s0;
-    if (wave_idle) {
-      // No row of this wavefront belongs to a token (the last token tile of a request is padded to 256 rows): it
-      // only keeps its part of the tile pipeline going - the same loads, waits and barriers per tile as below.
-      for (; kt < s1; ++kt) {
-        issue_before_sync(t2, buf_of(kt - s0 + 2));
-        sync_next();
-        const Tile t3 = tile_ahead(kt + 3);
-        issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
-        t2 = t3;
-      }
-    } else if (kt < nf) {
-      // Reference maxima for the fast tiles: the column maxima of the first 32 keys.  fp16 weights have a short
-      // exponent range (2^-24 .. 2^16), and only an overflow is noticed afterwards (rows whose later scores outgrow
-      // the representable range are caught below), never an underflow: the reference sits 8 units BELOW the maxima,
-      // so that a key as good as the first ones weighs 2^8, later keys may exceed them by 2^8 more before the
-      // fallback is taken, and keys 2^22 times lighter than the first ones still keep every bit.
-      u32x4 k0[KS];
-      static_for<0, KS>([&](auto ks) { k0[ks] = read_k(ks, lds_t0, 0); });
-      {
-        f32x16 s[2];
-        float tmax[2];
-        zero(s[0]);
-        zero(s[1]);
-        static_for<0, KS>([&](auto ks) {
-          s[0] = PElem<DT>::mfma(k0[ks], qf[0][ks], s[0]);
-          s[1] = PElem<DT>::mfma(k0[ks], qf[1][ks], s[1]);
-        });
-        block_max(s, tmax);
-        m_used[0] = tmax[0] - (DT == VT_F16 ? 8.0f : 0.0f);
-        m_used[1] = tmax[1] - (DT == VT_F16 ? 8.0f : 0.0f);
-      }
-      for (;;) {
-        fast_tile(std::false_type{}, kt, lds_t0, lds_t1, lds_t2, lds_t3, k0, t2);
-        if (++kt >= nf) break;
-        fast_tile(std::false_type{}, kt, lds_t1, lds_t2, lds_t3, lds_t0, k0, t2);
-        if (++kt >= nf) break;
-        fast_tile(std::false_type{}, kt, lds_t2, lds_t3, lds_t0, lds_t1, k0, t2);
-        if (++kt >= nf) break;
-        fast_tile(std::false_type{}, kt, lds_t3, lds_t0, lds_t1, lds_t2, k0, t2);
-        if (++kt >= nf) break;
-      }
-      // The masked tiles that follow fast ones keep the fixed reference maxima (every row has one by now) and
-      // the same instruction schedule, with the mask applied to the weights.
-      for (; kt < s1; ++kt)
-        fast_tile(std::true_type{}, kt, buf_of(kt - s0), buf_of(kt - s0 + 1), buf_of(kt - s0 + 2), buf_of(kt - s0 + 3),
-                  k0, t2);
-    }
-    for (; kt < s1; ++kt) {
-      issue_before_sync(t2, buf_of(kt - s0 + 2));
-      generic_tile(buf_of(kt - s0), tile_of(kt));
-      sync_next();
-      const Tile t3 = tile_ahead(kt + 3);
-      issue_after_sync(t2, t3, buf_of(kt - s0 + 2), buf_of(kt - s0 + 3));
-      t2 = t3;
-    }
-    // drain the repeated refills before anything else is loaded into the buffers
-    wait_loads(std::integral_constant<int, 0>{});
-    if (attempt > 0 || nf <= s0) break;
-    // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones:
-    // then some sum or accumulator is no longer finite and the whole workgroup redoes the piece the classic way.
-    float chk = l_run[0] + l_run[1];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) chk += __builtin_fabsf(acc[db][cb][i]);
-    if (!__syncthreads_or(!(chk < INFINITY))) break;
-    nf = s0;
-  }
-
-  // Nobody reads the tile buffers any more once every wavefront is here; the next piece may then load into them
-  // while this one's results are still on their way out (bare barrier: no wait for the stores below).
-  __builtin_amdgcn_s_barrier();
-
-  // acc[db][cb][i] is d = 32*db + 8*(i/4) + 4*hi + i%4 of the lane's query row.
-  if (whole) {
-    // out[row, d] = acc / l.  The rows go through LDS (the tile buffers are free now; each wavefront uses its own),
-    // so that the global stores are whole 16-byte pieces of contiguous rows rather than 8 bytes per lane scattered
-    // over 32 rows.
-    constexpr int STG = ROWB + 16;  // staging row stride
-    char* stg = buf_of(wave);
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
-      const float inv = 1.0f / l_tot;
-      char* sp = stg + (cb * 32 + col) * STG + 8 * hi;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int cb = 0; cb < 2; ++cb) {
+        char* sp = stg + (cb * 32 + col) * STG + 8 * hi;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           u32x2 w;
-          w[0] = PElem<DT>::pack2(acc[db][cb][4 * q4] * inv, acc[db][cb][4 * q4 + 1] * inv);
-          w[1] = PElem<DT>::pack2(acc[db][cb][4 * q4 + 2] * inv, acc[db][cb][4 * q4 + 3] * inv);
-          *(u32x2*)(sp + (32 * db + 8 * q4) * 2) = w;
+          w[0] = PElem<DT>::pack2(acc[db][cb][4 * q4] * inv[cb], acc[db][cb][4 * q4 + 1] * inv[cb]);
+          w[1] = PElem<DT>::pack2(acc[db][cb][4 * q4 + 2] * inv[cb], acc[db][cb][4 * q4 + 3] * inv[cb]);
+          *(u32x2*)(sp + 16 * q4) = w;
         }
-    }
-    // (LDS operations of one wavefront complete in order: no barrier between the writes above and these reads)
-    const unsigned g_magic = (65536u + (unsigned)G - 1u) / (unsigned)G;  // r / G for r < 256
-    constexpr int RPS = 64 / CH;  // rows per store instruction
-#pragma unroll
-    for (int i = 0; i < 64 / RPS; ++i) {
-      const int rl = i * RPS + lane / CH, ch = lane % CH;
-      const int rr = wave * 64 + rl;
-      const int t = (int)(((unsigned)rr * g_magic) >> 16), head = rr - t * G;
-      const u32x4 v = *(const u32x4*)(stg + rl * STG + ch * 16);
-      if (t < ntok)
-        *(u32x4*)(p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)g * G + head) * ROWB + ch * 16) = v;
-    }
-    // The staging rows lie in tile buffers that every wavefront loads into: nobody may start the next piece's
-    // loads before all staged rows have been read back (the values are in registers by now; the stores go on).
-    __builtin_amdgcn_s_barrier();
-  } else {
-    // A piece: reference maxima, sums and unnormalised accumulators of its rows go to the slot (the merge pass
-    // never looks at padding rows).
-    float* sl = p.ws + (size_t)slot * piece_floats(D);
-#pragma unroll
-    for (int cb = 0; cb < 2 && !wave_idle; ++cb) {
-      const float l_tot = l_run[cb] + __shfl_xor(l_run[cb], 32);
-      const int r = wave * 64 + cb * 32 + col;
-      if (hi == 0) {
-        sl[r] = m_used[cb];
-        sl[256 + r] = l_tot;
       }
-      float* ap = sl + 512 + (size_t)r * D;
+      // (LDS operations of one wavefront complete in order: no barrier between the writes above and these reads,
+      // nor between these reads and the next round's writes)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int rl = 16 * i + lane / 4, ch = lane % 4;
+        const int rr = wave * 64 + rl;
+        const int t = (int)(((unsigned)rr * g_magic) >> 16), head = rr - t * G;
+        const u32x4 v = *(const u32x4*)(stg + rl * STG + ch * 16);
+        if (t < nt)
+          *(u32x4*)(p.out + ((size_t)(pc.cu_b + tok0 + t) * p.hq + (size_t)pc.g * G + head) * ROWB + db * 64 +
+                    ch * 16) = v;
+      }
+    }
+  };
+
+  // Piece slots in the workspace.  A slot holds, for the 256 rows, the reference maxima, the sums and the
+  // unnormalised accumulators of one piece in the order the lanes hold them: thread t's accumulator values
+  // (db, cb, 4 consecutive i) are the 16 bytes at block ((db*2 + cb)*4 + i/4), position t - every store and load of
+  // the workgroup covers 4 KiB contiguous.  Rows are the same in every workgroup (row = 64*wave + 32*cb + col).
+  auto slot_of = [&](uint32_t owner, bool head) -> float* {
+    return p.ws + (size_t)(2 * owner + (head ? 1u : 0u)) * piece_floats(D);
+  };
+
+  int gt = 0;           // position of the current tile in the stream; its buffer is gt % 4
+  bool primed = false;  // the first tiles of the piece are already on their way (issued by the previous piece)
+  for (;;) {
+    // ---- the piece: tiles s0 .. s1-1 of item (b, g, t) ----
+    s0 = cur.s0;
+    s1 = cur.s1;
+    P = cur.P;
+    const int tok0 = cur.t * tb;
+    ntok = min(tb, cur.N - tok0);
+    const int nfast_item = cur.fastA + cur.fastB;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const int t = (wave * 64 + cb * 32 + col) / G;
+      lim[cb] = P + tok0 + min(t, ntok - 1);  // key j is visible iff j <= lim
+    }
+    // Rows past the last token of the tile are padding; a wavefront whose 64 rows are all padding computes nothing.
+    wave_idle = (wave * 64) / G >= ntok;
+    // The tiles after this piece are first asked for by its third-last tile; in a piece of four tiles or more the
+    // look-up runs beside the second tile (scalar work next to the matrix pipe) instead of in front of the first.
+    int park_at = s1 - s0 >= 4 ? s0 + 1 : s0 - 1;
+    if (park_at < s0) park_ahead();
+
+    // Fast tiles of this piece: s0 .. nf-1.
+    int nf = min(s1, nfast_item);
+    Piece nxt;
+    u32x4 qn[2][KS];
+    for (int attempt = 0;; ++attempt) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 w;
-          w[0] = acc[db][cb][4 * q4];
-          w[1] = acc[db][cb][4 * q4 + 1];
-          w[2] = acc[db][cb][4 * q4 + 2];
-          w[3] = acc[db][cb][4 * q4 + 3];
-          *(f32x4*)(ap + 32 * db + 8 * q4 + 4 * hi) = w;
-        }
-    }
-  }
-  }  // piece loop
-  if (tid == 0) shared_items[group] = my_shared;
-}
+        for (int cb = 0; cb < 2; ++cb) zero(acc[db][cb]);
+      m_used[0] = m_used[1] = -INFINITY;
+      l_run[0] = l_run[1] = 0.f;
 
-// Merges the pieces of every item that is shared between workgroups.  Workgroups (w, y) of this kernel look at
-// the record workgroup w of the main kernel left: if an item began in its range and ended in a later one, they
-// merge its pieces - the first one in slot 2w+1, then slot 2u of every following workgroup u that owns tiles of
-// it - for rows 32y .. 32y+31.  With maxima m_p, sums l_p and accumulators a_p of the pieces and M = max m_p:
-// out = sum_p a_p 2^(m_p - M) / sum_p l_p 2^(m_p - M).
-template <int DT, int D>
-__global__ __launch_bounds__(256) void prefill_combine_kernel(PrefillParams p) {
-  const int tid = threadIdx.x;
-  const uint32_t w = blockIdx.x;
-  const SharedItem it = ((const SharedItem*)(p.ws + (size_t)2 * p.n_groups * piece_floats(D)))[w];
-  if (!it.valid) return;
-  ItemShape sh;
-  sh.nkt = it.nkt;
-  sh.nfast = it.nfast;
-  const uint32_t cost = item_cost(sh);
-  const int G = (int)p.group, tb = (int)p.tb;
-  const int cu_b = p.cu[it.b], N = p.cu[it.b + 1] - cu_b;
-  const int tok0 = it.t * tb, ntok = min(tb, N - tok0);
-  // A thread merges 16 consecutive d of one row (four float4); blockIdx.y picks the rows.
-  constexpr int TPR = D / 16;        // threads per row
-  constexpr int RPB = 256 / TPR;     // rows per workgroup
-  const int r = (int)blockIdx.y * RPB + tid / TPR, d0 = 16 * (tid % TPR);
-  const int t = r / G, head = r - t * G;
-  if (t >= ntok) return;
-  float M = -INFINITY, den = 0.f;
-  f32x4 num[4];
+      Tile t2;
+      if (!primed) {
+        issue_tile(tile_ahead(s0), buf_of(gt), buf_of(gt) + TILEB);
+        issue_tile(tile_ahead(s0 + 1), buf_of(gt + 1), buf_of(gt + 1) + TILEB);
+        t2 = tile_ahead(s0 + 2);
+        issue_part(part0, t2, buf_of(gt + 2), buf_of(gt + 2) + TILEB);
+        wait_loads(std::integral_constant<int, VM + 2>{});
+        __builtin_amdgcn_s_barrier();
+        primed = true;
+      } else {
+        // (the last tile of the previous piece left tile s0 landed, s0+1 issued and the first load of s0+2 issued)
+        t2 = tile_ahead(s0 + 2);
+      }
+      // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
+      // the vector registers to the scores, the weights and the in-flight LDS operand reads.  They are pinned
+      // there only now, so that their loads and the first tiles' loads are in flight together.
 #pragma unroll
-  for (int k = 0; k < 4; ++k) num[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // two passes over the pieces: the maximum, then the weighted sums
-  for (int pass = 0; pass < 2; ++pass) {
-    for (uint32_t u = w; u < p.n_groups; ++u) {
-      const uint32_t ub = group_begin(p.total_cost, p.n_groups, u), ue = group_begin(p.total_cost, p.n_groups, u + 1);
-      const uint32_t c0 = u == w ? 0u : ub - it.cost_begin;
-      const uint32_t c1 = min(cost, ue - it.cost_begin);
-      if (tile_at(sh, c1) > tile_at(sh, c0)) {
-        const float* sl = p.ws + (size_t)(u == w ? 2 * u + 1 : 2 * u) * piece_floats(D);
-        const float m = sl[r];
-        if (pass == 0) {
-          M = fmaxf(M, m);
-        } else {
-          const float wgt = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
-          den += wgt * sl[256 + r];
-          const f32x4* ap = (const f32x4*)(sl + 512 + (size_t)r * D + d0);
+      for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-          for (int k = 0; k < 4; ++k) num[k] += ap[k] * wgt;
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
+      int kt = s0;
+      if (wave_idle) {
+        // No row of this wavefront belongs to a token (the last token tile of a request is padded to 256 rows): it
+        // only keeps its part of the tile pipeline going - the same loads, waits and barriers per tile as below.
+        for (; kt < s1; ++kt, ++gt) {
+          if (kt == park_at) park_ahead();
+          issue_before_sync(t2, buf_of(gt + 2));
+          sync_next();
+          const Tile t3 = tile_ahead(kt + 3);
+          issue_after_sync(t2, t3, buf_of(gt + 2), buf_of(gt + 3));
+          t2 = t3;
+        }
+      } else if (kt < nf) {
+        // Reference maxima for the fast tiles: the column maxima of the first 32 keys.  fp16 weights have a short
+        // exponent range (2^-24 .. 2^16), and only an overflow is noticed afterwards (rows whose later scores
+        // outgrow the representable range are caught below), never an underflow: the reference sits 8 units BELOW
+        // the maxima, so that a key as good as the first ones weighs 2^8, later keys may exceed them by 2^8 more
+        // before the fallback is taken, and keys 2^22 times lighter than the first ones still keep every bit.
+        u32x4 k0[KS];
+        {
+          const char* first = buf_of(gt);
+          static_for<0, KS>([&](auto ks) { k0[ks] = read_k(ks, first, 0); });
+          f32x16 s[2];
+          float tmax[2];
+          zero(s[0]);
+          zero(s[1]);
+          static_for<0, KS>([&](auto ks) {
+            s[0] = PElem<DT>::mfma(k0[ks], qf[0][ks], s[0]);
+            s[1] = PElem<DT>::mfma(k0[ks], qf[1][ks], s[1]);
+          });
+          block_max(s, tmax);
+          m_used[0] = tmax[0] - (DT == VT_F16 ? 8.0f : 0.0f);
+          m_used[1] = tmax[1] - (DT == VT_F16 ? 8.0f : 0.0f);
+        }
+        for (; kt < nf; ++kt, ++gt) {
+          if (kt == park_at) park_ahead();
+          fast_tile(std::false_type{}, kt, buf_of(gt), buf_of(gt + 1), buf_of(gt + 2), buf_of(gt + 3), k0, t2);
+        }
+        // The masked tiles that follow fast ones keep the fixed reference maxima (every row has one by now) and
+        // the same instruction schedule, with the mask applied to the weights.
+        for (; kt < s1; ++kt, ++gt) {
+          if (kt == park_at) park_ahead();
+          fast_tile(std::true_type{}, kt, buf_of(gt), buf_of(gt + 1), buf_of(gt + 2), buf_of(gt + 3), k0, t2);
         }
       }
-      if (ue - it.cost_begin >= cost) break;
-    }
-  }
-  const float inv = 1.0f / den;
-  u32x4 o[2];
+      for (; kt < s1; ++kt, ++gt) {
+        if (kt == park_at) park_ahead();
+        issue_before_sync(t2, buf_of(gt + 2));
+        generic_tile(buf_of(gt), tile_of(kt));
+        sync_next();
+        const Tile t3 = tile_ahead(kt + 3);
+        issue_after_sync(t2, t3, buf_of(gt + 2), buf_of(gt + 3));
+        t2 = t3;
+      }
+      // The next piece, and its query rows on their way while this piece's results go out.
+      if (attempt == 0) {
+        nxt = next_piece(cur);
+        if (nxt.valid) load_q(nxt, qn);
+      }
+      if (attempt > 0 || nf <= s0) break;
+      // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones: then
+      // some sum or accumulator is no longer finite and the whole workgroup redoes the piece the classic way.
+      float chk = l_run[0] + l_run[1];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    o[k / 2][2 * (k % 2)] = PElem<DT>::pack2(num[k][0] * inv, num[k][1] * inv);
-    o[k / 2][2 * (k % 2) + 1] = PElem<DT>::pack2(num[k][2] * inv, num[k][3] * inv);
-  }
-  char* op = p.out + ((size_t)(cu_b + tok0 + t) * p.hq + (size_t)it.g * G + head) * (D * 2) + d0 * 2;
-  ((u32x4*)op)[0] = o[0];
-  ((u32x4*)op)[1] = o[1];
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) chk += __builtin_fabsf(acc[db][cb][i]);
+      const bool bad = __builtin_amdgcn_ballot_w64(!(chk < INFINITY)) != 0;
+      if (lane == 0) s_vote[wave] = bad ? 1 : 0;
+      lds_barrier();
+      const int any_bad = uni(s_vote[0] | s_vote[1] | s_vote[2] | s_vote[3]);
+      lds_barrier();  // (nobody writes the votes of the next piece before everybody has read these)
+      if (!any_bad) break;
+      // Start over from the piece's first tile: nothing may be in flight into the buffers, nobody may still read them.
+      wait_loads(std::integral_constant<int, 0>{});
+      __builtin_amdgcn_s_barrier();
+      primed = false;
+      nf = s0;
+    }
+
+    float l_tot[2] = {l_run[0] + __shfl_xor(l_run[0], 32), l_run[1] + __shfl_xor(l_run[1], 32)};
+    bool finish = s0 == 0 && s1 == cur.nkt;  // the piece is the whole item
+    if (!finish) {
+      // The item is shared with other workgroups.  Its pieces meet in the workspace: whoever finishes a piece adds
+      // one to the item's arrival count; the one who finds all the others already there merges their slots into its
+      // own registers and writes the output, everybody else leaves the piece in its slot.  Nobody waits for anybody.
+      // The count lives in the word of the group that owns the item's first tile, tagged with the number of this
+      // launch (a count left by an earlier launch reads as zero).
+      const uint32_t n = p.n_groups, total = p.total_cost;
+      const uint32_t unit0 = cur.item_begin + (uint32_t)kItemCost;  // first cost unit of the item's first tile
+      uint32_t w0 = (uint32_t)((((uint64_t)unit0 + 1) * n - 1) / total);
+      while (group_begin(total, n, w0 + 1) <= unit0) ++w0;
+      while (group_begin(total, n, w0) > unit0) --w0;
+      ItemShape sh;
+      sh.nkt = cur.nkt;
+      sh.nfast = cur.nfast;
+      const uint32_t cost = item_cost(sh);
+      // groups w0 .. w_last hold tiles of the item; `others` of them apart from this one
+      uint32_t w_last = w0, pieces = 0;
+      for (uint32_t u = w0;; ++u) {
+        const uint32_t c0 = u == w0 ? 0u : group_begin(total, n, u) - cur.item_begin;
+        const uint32_t c1 = min(cost, group_begin(total, n, u + 1) - cur.item_begin);
+        if (tile_at(sh, c1) > tile_at(sh, c0)) {
+          ++pieces;
+          w_last = u;
+        }
+        if (c1 >= cost) break;
+      }
+      unsigned long long* word = p.arrivals + w0;
+      const unsigned long long tag = p.launch << 16;
+      auto count_of = [&](unsigned long long v) -> uint32_t { return (v >> 16) == p.launch ? (uint32_t)(v & 0xffffu) : 0u; };
+      if (tid == 0)
+        s_arrived = count_of(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      lds_barrier();
+      bool last = (uint32_t)uni((int)s_arrived) == pieces - 1;
+      lds_barrier();
+      if (!last) {
+        // leave the piece in the slot (stores that go through to memory), wait until they have landed, then count it
+        float* sl = slot_of(group, group == w0);
+        if (!wave_idle) {
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            if (hi == 0) {
+              __hip_atomic_store(sl + wave * 64 + cb * 32 + col, m_used[cb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              __hip_atomic_store(sl + 256 + wave * 64 + cb * 32 + col, l_tot[cb], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 w = {acc[db][cb][4 * q4], acc[db][cb][4 * q4 + 1], acc[db][cb][4 * q4 + 2],
+                                 acc[db][cb][4 * q4 + 3]};
+                store16_device(sl + 512 + (size_t)(((db * 2 + cb) * 4 + q4) * 256 + tid) * 4, w);
+              }
+          }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        if (tid == 0) {
+          unsigned long long seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          uint32_t before;
+          do {
+            before = count_of(seen);
+          } while (!__hip_atomic_compare_exchange_strong(word, &seen, tag | (before + 1), __ATOMIC_RELAXED,
+                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          s_arrived = before;
+        }
+        lds_barrier();
+        last = (uint32_t)uni((int)s_arrived) == pieces - 1;
+        lds_barrier();
+      }
+      if (last) {
+        if (!wave_idle) {
+          for (uint32_t u = w0; u <= w_last; ++u) {
+            if (u == group) continue;
+            const uint32_t c0 = u == w0 ? 0u : group_begin(total, n, u) - cur.item_begin;
+            const uint32_t c1 = min(cost, group_begin(total, n, u + 1) - cur.item_begin);
+            if (tile_at(sh, c1) <= tile_at(sh, c0)) continue;
+            const float* sl = slot_of(u, u == w0);
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+              const int r = wave * 64 + cb * 32 + col;
+              f32x4 o[4 * DB];
+#pragma unroll
+              for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                  load16_device(o[4 * db + q4], sl + 512 + (size_t)(((db * 2 + cb) * 4 + q4) * 256 + tid) * 4);
+              const float m_o = __hip_atomic_load(sl + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              const float l_o = __hip_atomic_load(sl + 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              static_assert(DB == 4 || DB == 2, "operand list below");
+              if constexpr (DB == 4)
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]),
+                               "+v"(o[7]), "+v"(o[8]), "+v"(o[9]), "+v"(o[10]), "+v"(o[11]), "+v"(o[12]), "+v"(o[13]),
+                               "+v"(o[14]), "+v"(o[15])
+                             :
+                             : "memory");
+              else
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]), "+v"(o[4]), "+v"(o[5]), "+v"(o[6]),
+                               "+v"(o[7])
+                             :
+                             : "memory");
+              const float m_new = fmaxf(m_used[cb], m_o);
+              // (a side that has seen no key has no maximum: weight 0, and never the exponential of inf - inf)
+              const float a = m_used[cb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_used[cb] - m_new);
+              const float bwt = m_o == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_o - m_new);
+              m_used[cb] = m_new;
+              l_tot[cb] = l_tot[cb] * a + l_o * bwt;
+#pragma unroll
+              for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                  for (int i = 0; i < 4; ++i)
+                    acc[db][cb][4 * q4 + i] = acc[db][cb][4 * q4 + i] * a + o[4 * db + q4][i] * bwt;
+            }
+          }
+        }
+        finish = true;
+      }
+    }
+    if (finish) {
+      const float inv[2] = {1.0f / l_tot[0], 1.0f / l_tot[1]};
+      write_rows(cur, inv);
+    }
+    if (!nxt.valid) break;
+    cur = nxt;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = qn[cb][ks];
+  }  // piece loop
+  // nothing may still be on its way into LDS when the workgroup ends
+  wait_loads(std::integral_constant<int, 0>{});
 }
 
 }  // namespace
@@ -969,7 +1205,7 @@ int plan_prefill(const vt_ctx* ctx, const int32_t* cu_host, const int32_t* plens
   out->n_tiles = tiles;
   out->n_items = (uint32_t)items;
   out->n_groups = total ? (uint32_t)groups : 0;
-  out->workspace_bytes = total ? 2 * groups * piece_floats((int)d) * sizeof(float) + groups * sizeof(SharedItem) : 0;
+  out->workspace_bytes = total ? 2 * groups * piece_floats((int)d) * sizeof(float) : 0;
   uint64_t count = 0;
   if ((pieces || n_pieces) && total) {
     // walk the items once, carving each at the group boundaries that fall inside it
@@ -1039,26 +1275,23 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   p.q_sign = a->scale < 0.0f ? 0x80008000u : 0u;
   p.total_cost = (uint32_t)plan.total_cost;
   p.n_groups = plan.n_groups;
-  const uint64_t groups = plan.n_groups;
   rc = ensure_workspace(ctx, plan.workspace_bytes);
   if (rc != VT_OK) return rc;
+  if (!ctx->arrivals || plan.n_groups > kMaxPrefillGroups) return VT_E_UNSUPPORTED;
   p.ws = (float*)ctx->ws;
+  p.arrivals = (unsigned long long*)ctx->arrivals;
+  p.launch = ++ctx->prefill_launches;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid(p.n_groups), cgrid(p.n_groups, a->head_dim / 16), block(256);
+  const dim3 grid(p.n_groups), block(256);
   prof_begin(ctx, 1, st);
-  if (a->dtype == VT_BF16 && a->head_dim == 128) {
+  if (a->dtype == VT_BF16 && a->head_dim == 128)
     hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128>), grid, block, 0, st, p);
-    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_BF16, 128>), cgrid, block, 0, st, p);
-  } else if (a->dtype == VT_BF16 && a->head_dim == 64) {
+  else if (a->dtype == VT_BF16 && a->head_dim == 64)
     hipLaunchKernelGGL((prefill_kernel<VT_BF16, 64>), grid, block, 0, st, p);
-    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_BF16, 64>), cgrid, block, 0, st, p);
-  } else if (a->dtype == VT_F16 && a->head_dim == 128) {
+  else if (a->dtype == VT_F16 && a->head_dim == 128)
     hipLaunchKernelGGL((prefill_kernel<VT_F16, 128>), grid, block, 0, st, p);
-    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_F16, 128>), cgrid, block, 0, st, p);
-  } else {
+  else
     hipLaunchKernelGGL((prefill_kernel<VT_F16, 64>), grid, block, 0, st, p);
-    if (groups > 1) hipLaunchKernelGGL((prefill_combine_kernel<VT_F16, 64>), cgrid, block, 0, st, p);
-  }
   prof_end(ctx, st);
   return hipGetLastError() == hipSuccess ? VT_OK : VT_E_DRIVER;
 }

@@ -94,41 +94,75 @@ def test_tiles_cover_every_visible_pair_once_and_fast_tiles_need_no_mask(split):
                            for k in tile for i in range(ntok))
 
 
-@pytest.mark.parametrize("cfg_id,split", [(3, True), (4, True), (3, False)])
-def test_every_tile_is_computed_once_and_shares_are_even(ctx, cfg_id, split):
-    cu, P = lens_of(cfg_id)
-    cfg = CONFIGS[cfg_id]
-    plan, pieces = vt.vt_plan_prefill(ctx, cu, P, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
-                                      new_rows_in_cache=not split, want_pieces=True)
+def check_decomposition(pieces, total_cost, n_tiles, n_items, n_groups, P, N_of, tb, split):
+    """What must hold of any such decomposition, whoever computed it.  pieces: (group, request, kv_head,
+    token_tile, tile_begin, tile_end) in execution order.  The tile counts per item come from the tile enumeration
+    of the rule (itself pinned by brute force above)."""
+    shape = {}
+    def tiles_of(r, t):
+        if (r, t) not in shape:
+            shape[(r, t)] = meta.prefill_item_tiles(int(P[r]), int(N_of(r)), t, tb, split)
+        return shape[(r, t)]
     # coverage: per item the pieces tile [0, n_tiles) without gap or overlap, in increasing groups
     by_item = {}
-    for p in pieces:
-        by_item.setdefault((p.request, p.kv_head, p.token_tile), []).append(p)
-    assert len(by_item) == plan.n_items
-    for key, ps in by_item.items():
-        assert ps[0].tile_begin == 0 and ps[-1].tile_end == ps[0].n_tiles
+    for pc in pieces:
+        by_item.setdefault(pc[1:4], []).append(pc)
+    assert len(by_item) == n_items
+    for (r, g, t), ps in by_item.items():
+        nt = len(tiles_of(r, t))
+        assert ps[0][4] == 0 and ps[-1][5] == nt
         for a, b in zip(ps, ps[1:]):
-            assert a.tile_end == b.tile_begin and a.group < b.group
-        assert all(p.tile_end > p.tile_begin for p in ps)
-    assert sum(p.tile_end - p.tile_begin for p in pieces) == plan.n_tiles
+            assert a[5] == b[4] and a[0] < b[0]
+        assert all(pc[5] > pc[4] for pc in ps)
+    assert sum(pc[5] - pc[4] for pc in pieces) == n_tiles
     # a group continues at most one item (first) and leaves at most one unfinished (last)
     groups = {}
-    for p in pieces:
-        groups.setdefault(p.group, []).append(p)
+    for pc in pieces:
+        groups.setdefault(pc[0], []).append(pc)
+    assert all(0 <= w < n_groups for w in groups)
     for w, ps in groups.items():
-        assert all(p.tile_begin == 0 for p in ps[1:])
-        assert all(p.tile_end == p.n_tiles for p in ps[:-1])
-    # even shares: a group's cost (2 per fast tile, 3 per other, 8 per started item) stays within one tile and
-    # one item start of the ideal share
-    ideal = plan.total_cost / plan.n_groups
+        assert all(pc[4] == 0 for pc in ps[1:])
+        assert all(pc[5] == len(tiles_of(pc[1], pc[3])) for pc in ps[:-1])
+    # even shares: a group's cost (per fast tile, per other tile, per started item) stays within one tile and one
+    # item start of the ideal share
+    cf, cm, ci = meta.PREFILL_COST_FAST, meta.PREFILL_COST_MASKED, meta.PREFILL_COST_ITEM
+    ideal = total_cost / n_groups
     for w, ps in groups.items():
         c = 0
-        for p in ps:
-            fast = max(0, min(p.tile_end, p.n_fast) - p.tile_begin)
-            c += 2 * fast + 3 * (p.tile_end - p.tile_begin - fast) + (8 if p.tile_begin == 0 else 0)
-        assert abs(c - ideal) <= 3 + 8 + 1, (w, c, ideal)
-    # workspace: two piece slots and one record per group
-    assert plan.workspace_bytes == plan.n_groups * (2 * (512 + 256 * cfg.head_dim) * 4 + 32)
+        for pc in ps:
+            flags = tiles_of(pc[1], pc[3])[pc[4]:pc[5]]
+            c += sum(cf if f else cm for f in flags) + (ci if pc[4] == 0 else 0)
+        assert abs(c - ideal) <= cm + ci + 1, (w, c, ideal)
+
+
+@pytest.mark.parametrize("cfg_id,split", [(3, True), (4, True), (3, False)])
+def test_every_tile_is_computed_once_and_shares_are_even(ctx, cfg_id, split):
+    """The properties are asserted on the rule's own output (oracle/meta.py, so that the rule is pinned by what any
+    decomposition must satisfy and not only by agreeing with the library) and on the library's output."""
+    cu, P = lens_of(cfg_id)
+    cfg = CONFIGS[cfg_id]
+    tb = 256 // (cfg.n_q_heads // cfg.n_kv_heads)
+    N_of = lambda r: cu[r + 1] - cu[r]
+    total, n_tiles, n_items, n_groups, ws, ref_pieces = meta.prefill_plan(cu, P, cfg.n_q_heads, cfg.n_kv_heads,
+                                                                          cfg.head_dim, split)
+    check_decomposition(ref_pieces, total, n_tiles, n_items, n_groups, P, N_of, tb, split)
+    plan, pieces = vt.vt_plan_prefill(ctx, cu, P, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                                      new_rows_in_cache=not split, want_pieces=True)
+    got = [(p.group, p.request, p.kv_head, p.token_tile, p.tile_begin, p.tile_end) for p in pieces]
+    check_decomposition(got, plan.total_cost, plan.n_tiles, plan.n_items, plan.n_groups, P, N_of, tb, split)
+    # workspace: two piece slots per group
+    assert plan.workspace_bytes == plan.n_groups * 2 * (512 + 256 * cfg.head_dim) * 4
+
+
+@pytest.mark.parametrize("name,plens,nlens,hq,hkv,d", CASES)
+def test_rule_properties_on_small_cases(name, plens, nlens, hq, hkv, d):
+    cu = np.concatenate([[0], np.cumsum(nlens)]).astype(np.int32)
+    P = np.array(plens, np.int32)
+    for split in (True, False):
+        for n_cus in (256, 7):
+            total, n_tiles, n_items, n_groups, ws, pieces = meta.prefill_plan(cu, P, hq, hkv, d, split, n_cus=n_cus)
+            check_decomposition(pieces, total, n_tiles, n_items, n_groups, P, lambda r: cu[r + 1] - cu[r],
+                                256 // (hq // hkv), split)
 
 
 def test_bad_arguments(ctx):
