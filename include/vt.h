@@ -3,12 +3,14 @@
  *
  * C ABI of libvt.  Method: "vTensor" (arXiv 2407.15309).  A request's K cache and V cache are each
  * ONE contiguous virtual address range sized for the maximum sequence length; physical memory is
- * attached to the range in fixed-size chunks as the sequence grows (paper Section 4.1), so the
+ * attached to the range in fixed-size chunks as the sequence grows (paper, "vTensor"), so the
  * attention kernels read plain arrays and need no page-table indirection.
  *
  * Conventions shared by every entry point
  *   - Returns a vt_status: 0 on success, negative on error.  Never throws, never aborts.  A call that
- *     fails leaves all library state as it was before the call.
+ *     fails leaves all library state as it was before the call; the exceptions are the calls that work through
+ *     a list of requests (vt_extend_batch, vt_extend_batch_async), which stop at the first request that fails and
+ *     keep the ones before it extended, as stated there.
  *   - "device" pointers are GPU addresses valid on the context's device; "host" pointers are ordinary
  *     process memory.  The library never takes ownership of caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The attention and append
@@ -16,8 +18,8 @@
  *     release / trim) are host-synchronous driver work and never touch bytes that are already mapped.
  *   - K/V layout: request b's K region is the row-major array [len_b, n_kv_heads, head_dim] of 16-bit
  *     elements, token stride n_kv_heads*head_dim elements; V likewise, in a separate region.
- *   - Query head h uses KV head h / (n_q_heads / n_kv_heads) (grouped-query attention, paper Section
- *     2.2.3; contiguous groups).
+ *   - Query head h uses KV head h / (n_q_heads / n_kv_heads) (grouped-query attention, paper "KV Cache
+ *     Optimization: GQA and MQA"; contiguous groups).
  *   - A vt_ctx may be used from several threads; region calls are serialised by an internal lock.
  *     Two attention calls on the same context must not overlap in time (they share one workspace).
  */
@@ -75,9 +77,9 @@ typedef struct {
 /* ---- context ------------------------------------------------------------------------------- */
 
 /* Creates a context on HIP device `device`.  chunk_bytes: physical chunk size, 0 => 2 MiB (the paper's
- * "2 MB", Section 4.1); must be a multiple of the device's minimum allocation granularity.
- * max_phys_bytes: cap on physical bytes held by the context, 0 => no cap.  Paper: Section 4.3, GPU
- * interface (reserve / create / map). */
+ * "2 MB", "vTensor"); must be a multiple of the device's minimum allocation granularity.
+ * max_phys_bytes: cap on physical bytes held by the context, 0 => no cap.  Paper: "vTensor Operation",
+ * Allocation, GPU interface (reserve / create / map). */
 int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_bytes);
 
 /* Same bookkeeping over HOST memory (mmap/memfd stand-ins for reserve/create/map), for tests of the
@@ -86,29 +88,29 @@ int vt_init(vt_ctx** out, int device, uint64_t chunk_bytes, uint64_t max_phys_by
 int vt_init_host(vt_ctx** out, uint64_t chunk_bytes, uint64_t max_phys_bytes);
 
 /* Unmaps and frees everything the context holds (all regions, pooled chunks, VA ranges, workspace).
- * Every vt_kv* of the context is invalid afterwards.  Paper: Section 4.3.2 (vFree, pFree at the end of
- * serving). */
+ * Every vt_kv* of the context is invalid afterwards.  Paper: "vTensor Operation", Deallocation (vFree, pFree at the
+ * end of serving). */
 int vt_destroy(vt_ctx* ctx);
 
-/* ---- regions (paper Sections 4.3 and 4.4) --------------------------------------------------- */
+/* ---- regions (paper, "vTensor Operation" and "vTensor Scheduler") ----------------------------- */
 
 /* vAlloc: reserves the K and V virtual ranges for one request, sized for max_tokens rows; maps nothing
  * (len = 0).  A free-listed range of the same size is reused before the driver is asked for a new one.
- * Paper: Section 4.3.1 vAlloc; Section 4.4 Create. */
+ * Paper: "vTensor Operation", vAlloc; "vTensor Scheduler", Create. */
 int vt_reserve(vt_ctx* ctx, uint32_t n_kv_heads, uint32_t head_dim, int dtype, uint64_t max_tokens, vt_kv** out);
 
 /* Extend: makes rows [0, new_len) backed, mapping ceil(new_len*row_bytes/chunk) chunks per region, pool
  * first, then new allocations (pAlloc + Map).  Grow-only: new_len < len => VT_E_INVALID; new_len >
  * max_tokens => VT_E_CAPACITY; over budget => VT_E_OOM with nothing changed.  Base pointers never move
- * and mapped bytes are never touched.  Paper: Section 4.3.1 pAlloc / Map; Section 4.4 Extend. */
+ * and mapped bytes are never touched.  Paper: "vTensor Operation", pAlloc / Map; "vTensor Scheduler", Extend. */
 int vt_extend(vt_kv* kv, uint64_t new_len_tokens);
 
 /* vt_extend for n requests in one call (one lock, one ABI crossing).  Stops at the first failure and
  * returns its status; requests before it stay extended, the failing one is unchanged. */
 int vt_extend_batch(vt_kv* const* kvs /*host [n]*/, const uint64_t* new_lens /*host [n]*/, uint32_t n);
 
-/* Asynchronous extension (paper Section 4.4: allocation runs asynchronously and overlaps computation; Section 5:
- * the scheduler dispatches the extension for coming tokens ahead of the kernels that need it).  vt_extend_batch_async queues the same work as vt_extend_batch for a worker
+/* Asynchronous extension (paper, "vTensor Scheduler", Extend: allocation runs asynchronously and overlaps
+ * computation; "FlexInfer Scheduler": the scheduler dispatches the extension for coming tokens ahead of the kernels that need it).  vt_extend_batch_async queues the same work as vt_extend_batch for a worker
  * thread of the context (requests run in the order queued) and returns at once with a ticket; the arrays are
  * copied.  vt_extend_wait blocks until that ticket and all earlier ones have run and returns the ticket's status
  * (VT_OK, or the error vt_extend_batch would have returned; later requests still run).  The driver's mapping calls
@@ -121,17 +123,17 @@ int vt_extend_wait(vt_ctx* ctx, uint64_t ticket);
  * the SAME physical chunks as `src`'s (mapped a second time, reference counted; no copy, no new
  * memory), and sets its len to n_tokens.  n_tokens*row_bytes must be a multiple of chunk_bytes unless
  * the caller never appends to `dst` (appends beyond n_tokens would otherwise write into the shared
- * last chunk): a non-aligned n_tokens returns VT_E_INVALID.  Paper: Section 4.4 Prefix Record and
- * Match; Section 4.2 pSet reference counts. */
+ * last chunk): a non-aligned n_tokens returns VT_E_INVALID.  Paper: "vTensor Scheduler", Prefix Record and
+ * Match; "vTensor Pool", pSet reference counts. */
 int vt_share_prefix(vt_kv* src, uint64_t n_tokens, uint64_t max_tokens, vt_kv** dst);
 
 /* Release: unmaps the request's chunks into the pool (a shared chunk returns to the pool when its last
  * mapping goes), puts the VA ranges on the free-list; no device memory is freed (lazy deallocation).
- * The handle is invalid afterwards.  Paper: Section 4.3.2; Section 4.4 Release. */
+ * The handle is invalid afterwards.  Paper: "vTensor Operation", Deallocation; "vTensor Scheduler", Release. */
 int vt_release(vt_kv* kv);
 
 /* pFree / vFree: really frees pooled chunks beyond `keep_pooled_chunks` and all free-listed VA ranges.
- * Paper: Section 4.3.2 (explicit memory-emptying). */
+ * Paper: "vTensor Operation", Deallocation (explicit memory-emptying). */
 int vt_trim(vt_ctx* ctx, uint64_t keep_pooled_chunks);
 
 int vt_query(const vt_kv* kv, vt_kv_info* out);
@@ -139,7 +141,7 @@ int vt_stats(const vt_ctx* ctx, vt_stats_t* out);
 
 /* KV-cache update: copies n_tokens rows [n_tokens, n_kv_heads, head_dim] from k_rows / v_rows (device
  * memory; host memory on a host context) into rows [at_token, at_token+n_tokens) of the regions, which
- * must already be backed (at_token + n_tokens <= len).  Enqueued on `stream`.  Paper: Section 2.1
+ * must already be backed (at_token + n_tokens <= len).  Enqueued on `stream`.  Paper: "LLM Inference"
  * (decode updates the KV cache). */
 int vt_append(vt_kv* kv, const void* k_rows, const void* v_rows, uint64_t n_tokens, uint64_t at_token, void* stream);
 
@@ -186,10 +188,11 @@ int vt_plan_decode(const vt_ctx* ctx, const int32_t* kv_lens_host, uint32_t batc
 
 /* Batched decode attention: out[b,h,:] = sum_j softmax_j(scale * <q[b,h,:], K_b[j,g(h),:]>) V_b[j,g(h),:]
  * over j in [0, kv_lens[b]).  Online softmax with fp32 accumulation over equal tape segments, followed by a merge of the requests that were cut.
- * Paper: Section 2.1 (decode stage), Section 6.2.1 (decoding kernel).  The context's workspace is grown
+ * Paper: "LLM Inference" (decode stage), "Decoding Kernel Evaluation".  The context's workspace is grown
  * on demand (growing it synchronises the device once; steady-state calls allocate nothing).
  * Errors: VT_E_INVALID for null pointers, n_q_heads % n_kv_heads != 0 or a host length < 1;
- * VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 256 and batch <= 4096. */
+ * a non-finite scale; VT_E_UNSUPPORTED unless head_dim is 64 or 128, n_q_heads/n_kv_heads <= 256 and
+ * batch <= 4096.  Any finite scale is taken (negative, zero). */
 int vt_attn_decode(vt_ctx* ctx, const vt_decode_args* args, void* stream);
 
 /* vt_attn_decode for callers that cannot allocate device memory: code under HIP graph capture, tight serving
@@ -226,8 +229,8 @@ typedef struct {
 
 /* Prefix-prefill attention: new token i of request b (absolute position P_b + i) attends keys
  * 0 .. P_b + i of concat(cached prefix, new tokens): the whole prefix plus the new tokens causally.
- * FlashAttention-style tiling on MFMA with fp32 accumulation.  Paper: Section 2.2.2 (prefix cache),
- * Section 6.2.2 (prefix-prefilling kernel).  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024, scale > 0. */
+ * FlashAttention-style tiling on MFMA with fp32 accumulation.  Paper: "Prefix Cache",
+ * "Prefix-prefilling Kernel Evaluation".  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024. */
 int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* stream);
 
 /* Integer work decomposition of a prefix-prefill call.  An item is (request, kv head, token tile of
@@ -238,8 +241,9 @@ int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* strea
  * tile - and group w of n_groups owns units [total_cost * w / n_groups, total_cost * (w+1) / n_groups) of
  * the items laid end to end (by request, kv head, token tile); a tile belongs to the owner of its first unit.
  * n_groups = clamp(total_cost / 64, 1, compute units).  One workgroup computes one group (which workgroup of the
- * launch takes which group is the kernel's business: it hands runs of consecutive groups to the same XCD).  An
- * item shared by several groups is merged by a second kernel from per-piece workspace slots. */
+ * launch takes which group is the kernel's business: it hands runs of consecutive groups to the same XCD).  The
+ * pieces of an item shared by several groups meet in per-piece workspace slots (two per group) and the workgroup
+ * that finishes its piece last merges them and writes the item's output. */
 typedef struct {
   uint64_t total_cost;
   uint64_t n_tiles;

@@ -2,8 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY; shares no code with the library.
 
-Region arithmetic follows the paper's vTensor description (Section 4.1 and the
-Allocation paragraph of Section 4.3): a request gets a virtual range sized for
+Region arithmetic follows the paper's vTensor description ("vTensor" and the
+Allocation paragraphs of "vTensor Operation"): a request gets a virtual range sized for
 the maximum sequence length, physical memory is attached in fixed-size chunks
 (2 MiB), and only as many chunks are mapped as the current length needs.
 

@@ -1,9 +1,10 @@
 // Batched decode attention over per-request contiguous K/V regions (gfx950).
 //
-// What is computed (paper Section 2.1, decode stage; Section 2.2.3 for grouped heads): for request b and
+// What is computed (paper "LLM Inference", decode stage; "KV Cache Optimization: GQA and MQA" for grouped
+// heads): for request b and
 // query head h, out = sum_j softmax_j(scale <q, k_j>) v_j over the request's cached rows, K/V row j of
 // KV head g living at base_b + (j*Hkv + g)*D.  Because a request's cache is one contiguous virtual
-// range (paper Section 4.1) the kernel addresses rows by plain pointer arithmetic.
+// range (paper "vTensor") the kernel addresses rows by plain pointer arithmetic.
 //
 // Work decomposition ("tape" split).  For every KV head the cached tokens of all requests, laid end to end,
 // form one tape of sum_b L_b tokens.  The tape is cut into n_seg equal segments of seg_len tokens and one
@@ -146,6 +147,11 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   __shared__ __attribute__((aligned(16))) char lds_all[kWaves][kTile * RSB];
   __shared__ int tape[kMaxDecodeBatch + 1];  // tape[b] = tokens of the requests before b
   __shared__ int wave_tot[kWaves];
+  // Region bases of the first requests, fetched beside the lengths: a piece of one of them starts its K/V loads
+  // without a second round trip to memory for the pointers.
+  constexpr int kPtrWin = 256;
+  __shared__ const char* s_kp[kPtrWin];
+  __shared__ const char* s_vp[kPtrWin];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int B = (int)p.batch, seg_len = (int)p.seg_len;
@@ -156,6 +162,10 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   // wavefront scan of the per-thread sums, then across wavefronts.
   {
     const int per = (B + 256) >> 8;
+    if (tid < kPtrWin && tid < B) {
+      s_kp[tid] = p.k_ptrs[tid];
+      s_vp[tid] = p.v_ptrs[tid];
+    }
     int sum = 0;
     for (int i = 0; i < per; ++i) {
       const int r = tid * per + i;
@@ -213,8 +223,8 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
     const int first = T0 / seg_len;
     d.index = sidx - first;
     d.count = (T0 + L - 1) / seg_len - first + 1;
-    d.kb = p.k_ptrs[b] + (size_t)g * D * 2 + cK * 16;
-    d.vb = p.v_ptrs[b] + (size_t)g * D * 2 + (c16 % CH) * 16;
+    d.kb = (b < kPtrWin ? s_kp[b] : p.k_ptrs[b]) + (size_t)g * D * 2 + cK * 16;
+    d.vb = (b < kPtrWin ? s_vp[b] : p.v_ptrs[b]) + (size_t)g * D * 2 + (c16 % CH) * 16;
   };
 
   Piece cur, nxt;
@@ -409,23 +419,71 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
 
 // Merge of a request's pieces (requests with a single piece were written by the main kernel):
 // M = max_s m_s; out = sum_s acc_s 2^(m_s-M) / sum_s l_s 2^(m_s-M).
-template <int DT, int D>
-__global__ __launch_bounds__(D) void decode_combine_kernel(DecodeParams p) {
-  const uint32_t h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+// One workgroup of W wavefronts per (request, query head).  A long request at a small batch is cut into hundreds of
+// pieces, and walking them one after the other is a chain of memory round trips: wavefront w takes pieces w, w+W,
+// ..., four of them in flight at a time, each lane D/64 of the row's values, keeps a running maximum with rescaled
+// sums, and the wavefronts' results meet in LDS.
+template <int DT, int D, int W>
+__global__ __launch_bounds__(64 * W) void decode_combine_kernel(DecodeParams p) {
+  constexpr int E = D / 64;  // values per lane
+  __shared__ float s_m[W], s_den[W];
+  __shared__ float s_num[W][D];
+  const uint32_t h = blockIdx.x, b = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int T0 = p.tape[b], L = p.tape[b + 1] - T0, seg_len = (int)p.seg_len;
   const int n = min((T0 + L - 1) / seg_len - T0 / seg_len + 1, (int)p.max_pieces);
   if (n <= 1) return;
   const size_t base = (size_t)b * p.max_pieces * p.hq + h;
-  float M = -INFINITY;
-  for (int s = 0; s < n; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.hq]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < n; ++s) {
-    const size_t idx = base + (size_t)s * p.hq;
-    const float w = __builtin_amdgcn_exp2f(p.part_m[idx] - M);
-    num += w * p.part_acc[idx * D + d];
-    den += w * p.part_l[idx];
+  float M = -INFINITY, den = 0.f, num[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) num[e] = 0.f;
+  for (int s = wave; s < n; s += 4 * W) {
+    float m4[4], l4[4], a4[4][E];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int su = s + u * W;
+      const bool valid = su < n;
+      const size_t idx = base + (size_t)(valid ? su : s) * p.hq;
+      m4[u] = valid ? p.part_m[idx] : -INFINITY;
+      l4[u] = p.part_l[idx];
+#pragma unroll
+      for (int e = 0; e < E; ++e) a4[u][e] = p.part_acc[idx * D + lane * E + e];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (m4[u] == -INFINITY) continue;  // (no such piece; every real piece holds at least one token)
+      const float m_new = fmaxf(M, m4[u]);
+      const float keep = __builtin_amdgcn_exp2f(M - m_new), w = __builtin_amdgcn_exp2f(m4[u] - m_new);
+      M = m_new;
+      den = den * keep + w * l4[u];
+#pragma unroll
+      for (int e = 0; e < E; ++e) num[e] = num[e] * keep + w * a4[u][e];
+    }
   }
-  ((unsigned short*)p.out)[((size_t)b * p.hq + h) * D + d] = Elem<DT>::cvt(num / den);
+  if (lane == 0) {
+    s_m[wave] = M;
+    s_den[wave] = den;
+  }
+#pragma unroll
+  for (int e = 0; e < E; ++e) s_num[wave][lane * E + e] = num[e];
+  __syncthreads();
+  if (wave != 0) return;
+  float Mx = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < W; ++w) Mx = fmaxf(Mx, s_m[w]);
+  float dsum = 0.f, nsum[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) nsum[e] = 0.f;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const float wt = s_m[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s_m[w] - Mx);
+    dsum += wt * s_den[w];
+#pragma unroll
+    for (int e = 0; e < E; ++e) nsum[e] += wt * s_num[w][lane * E + e];
+  }
+  unsigned short* o = (unsigned short*)p.out + ((size_t)b * p.hq + h) * D + lane * E;
+#pragma unroll
+  for (int e = 0; e < E; ++e) o[e] = Elem<DT>::cvt(nsum[e] / dsum);
 }
 
 __global__ void append_batch_kernel(char* const* k_ptrs, char* const* v_ptrs, const int32_t* kv_lens, const char* k_rows,
@@ -510,7 +568,12 @@ int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, 
   do {                                                                                           \
     hipLaunchKernelGGL((decode_kernel<DT, DD>), dim3(blocks), dim3(64 * kWaves), 0, st, p);      \
     if (allow_profile) prof_end(ctx, st);                                                        \
-    if (combine) hipLaunchKernelGGL((decode_combine_kernel<DT, DD>), cgrid, dim3(DD), 0, st, p); \
+    if (combine && plan.max_pieces <= 4)                                                         \
+      hipLaunchKernelGGL((decode_combine_kernel<DT, DD, 1>), cgrid, dim3(64), 0, st, p);         \
+    else if (combine && plan.max_pieces <= 16)                                                   \
+      hipLaunchKernelGGL((decode_combine_kernel<DT, DD, 4>), cgrid, dim3(256), 0, st, p);        \
+    else if (combine)                                                                            \
+      hipLaunchKernelGGL((decode_combine_kernel<DT, DD, 16>), cgrid, dim3(1024), 0, st, p);      \
   } while (0)
   if (a->dtype == VT_BF16 && a->head_dim == 128)
     VT_LAUNCH(VT_BF16, 128);

@@ -1,6 +1,6 @@
 // Region manager: per-request K and V virtual ranges backed by fixed-size physical chunks.
 //
-// Follows the paper's vTensor pool / operations (Sections 4.2-4.4): vAlloc reserves a range sized for
+// Follows the paper's "vTensor Pool", "vTensor Operation" and "vTensor Scheduler": vAlloc reserves a range sized for
 // the maximum sequence length and maps nothing; pAlloc takes idle chunks from the pool before asking
 // the driver for new ones; Map attaches chunks at the next offsets of the range; Release unmaps and
 // keeps everything for reuse (lazy deallocation); a chunk shared by several ranges is reference

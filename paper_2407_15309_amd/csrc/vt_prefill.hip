@@ -1,10 +1,10 @@
 // Prefix-prefill attention over per-request contiguous K/V regions (gfx950, MFMA).
 //
-// What is computed (paper Section 2.2.2, prefix cache; Section 6.2.2, prefix-prefilling kernel): new
+// What is computed (paper "Prefix Cache"; "Prefix-prefilling Kernel Evaluation"): new
 // token i of request b sits at absolute position P_b + i and attends keys 0 .. P_b + i of
 // concat(cached prefix rows, the new tokens' rows): the whole prefix without a mask, the new tokens
 // causally.  Prefix rows are read straight from the request's virtually contiguous region (paper
-// Section 4.1); the new tokens' rows come from k_new / v_new, or from the region itself when the caller
+// "vTensor"); the new tokens' rows come from k_new / v_new, or from the region itself when the caller
 // has already appended them.
 //
 // Tiling: a workgroup of 4 wavefronts computes 256 query rows of one (request, kv head) at a time: the G

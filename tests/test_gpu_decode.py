@@ -197,8 +197,23 @@ def test_any_finite_scale(ctx, scale):
         assert e.value.status == vt.VT_E_INVALID
 
 
+def test_paper_sweep_point_16k_batch16_gqa_32_4(ctx):
+    """One full point of the paper-shaped sweeps (KV length 16384, batch 16, the paper's default 32 query / 4 KV
+    heads), every output against the oracle; and batch 1 at the same length, where the request is cut into hundreds
+    of pieces and the merge kernel's many-wavefront path runs."""
+    cfg = CONFIGS[2].replace(batch=16, n_q_heads=32, n_kv_heads=4, kv_len=(16384, 16384))
+    check_decode(ctx, cfg, workloads.decode_inputs(cfg, seed=1604, threads=16), "sweep d1/d2 point")
+    cfg1 = cfg.replace(batch=1)
+    d1 = workloads.decode_inputs(cfg1, seed=1605)
+    plan, ns = vt.vt_plan_decode(ctx, d1["kv_lens"], 4, 32, 128)
+    assert ns.max() > 16                       # more pieces than the four-wavefront merge takes
+    check_decode(ctx, cfg1, d1, "sweep d1 batch 1")
+    cfg2 = cfg.replace(batch=3, dtype="f16", head_dim=64, n_q_heads=8, n_kv_heads=8, kv_len=(5000, 9000))
+    check_decode(ctx, cfg2, workloads.decode_inputs(cfg2, seed=1606), "many pieces f16 d64")
+
+
 def test_vmm_region_equals_plain_device_memory_bit_for_bit(ctx):
-    """To a kernel a region is an ordinary pointer (paper Section 4.1): same bytes, same result bits."""
+    """To a kernel a region is an ordinary pointer (paper "vTensor"): same bytes, same result bits."""
     cfg = CONFIGS[2].replace(batch=6, n_q_heads=32, n_kv_heads=8, kv_len=(300, 3000))
     data = workloads.decode_inputs(cfg, seed=77)
     reg = Regions(ctx, data["k"], data["v"], cfg.dtype)
@@ -236,7 +251,7 @@ def test_region_is_contiguous_over_scattered_chunks_on_device(ctx):
 
 def test_extend_changes_no_prior_output_and_never_moves_the_base(ctx):
     """Appending via vt_extend leaves decode over the old length bit-identical, also when the extension is
-    issued while a decode kernel over the old rows is still in flight (paper Section 4.4, Extend)."""
+    issued while a decode kernel over the old rows is still in flight (paper "vTensor Scheduler", Extend)."""
     cfg = CONFIGS[2].replace(batch=4, n_q_heads=32, n_kv_heads=8, kv_len=(900, 1100))
     data = workloads.decode_inputs(cfg, seed=5)
     reg = Regions(ctx, data["k"], data["v"], cfg.dtype, max_tokens=4096)
@@ -378,7 +393,7 @@ def test_config5_full_size_all_32_steps(ctx):
 
 
 def test_prefix_sharing_maps_the_same_chunks_into_a_second_region(ctx):
-    """Prefix match by aliasing (paper Section 4.4): the second request's region starts with the SAME physical
+    """Prefix match by aliasing (paper "vTensor Scheduler", Prefix Record and Match): the second request's region starts with the SAME physical
     chunks as the first one's - no copy, no new memory - then grows privately; decode over the shared prefix gives
     identical bits through either region."""
     cfg = CONFIGS[5].replace(batch=1, kv_len=(2048, 2048))      # 2 chunks of 1024 rows per region
@@ -429,7 +444,7 @@ def test_prefix_sharing_maps_the_same_chunks_into_a_second_region(ctx):
 
 
 def test_extension_overlaps_the_decode_steps(ctx):
-    """Paper Sections 4.4 / 5: memory for coming tokens is extended while the current step computes.  A decode loop
+    """Paper "vTensor Scheduler" (Extend) and "FlexInfer Scheduler": memory for coming tokens is extended while the current step computes.  A decode loop
     on a stream that does not synchronise with the default stream, (a) on regions extended beforehand, (b) with
     vt_extend_batch inside every step, (c) with the extension queued two steps ahead on the context's worker
     thread: the three produce identical bits, and the loops that extend take about as long as the one that does

@@ -125,6 +125,13 @@ def test_edge_lengths(ctx):
     check_prefill(ctx, cfg, d, "edges-mha-f16-d64")
 
 
+def test_paper_sweep_point_16k_context_ratio_half(ctx):
+    """One full point of the paper-shaped sweeps: context 16384, prefix ratio 0.5 (8192 cached + 8192 new tokens),
+    batch 1, the paper's default 32 query / 4 KV heads; every output row against the oracle."""
+    cfg, d = with_lens(CONFIGS[3].replace(n_q_heads=32, n_kv_heads=4), [8192], [8192], seed=1607)
+    check_prefill(ctx, cfg, d, "sweep p1 point")
+
+
 def test_one_item_shared_by_many_workgroups(ctx):
     """A single (request, kv head, token tile) with a long prefix: its key tiles are spread over several workgroups
     and the merge kernel combines more than two pieces."""

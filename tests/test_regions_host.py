@@ -1,6 +1,6 @@
 """Region bookkeeping of libvt on the host-memory backend (no GPU): reserve / extend / release / share /
 trim, error paths and rollback, checked against the oracle's integer model and the paper's statements
-about vTensor regions (Sections 4.1-4.4)."""
+about vTensor regions ("vTensor and Management")."""
 
 import ctypes as C
 import os
@@ -72,7 +72,7 @@ def test_chunk_count_is_exact_for_every_length(ctx):
 
 def test_virtual_range_is_contiguous_over_scattered_chunks(ctx):
     """A byte ramp written through the range reads back contiguous although the chunks come from the pool
-    in another order (paper Section 4.1: contiguous VA over non-contiguous physical chunks)."""
+    in another order (paper "vTensor": contiguous VA over non-contiguous physical chunks)."""
     a = vt.vt_reserve(ctx, 4, 64, vt.VT_F16, 2048)      # row 512 B, 128 rows per chunk
     vt.vt_extend(a, 128 * 5)
     ka = vt.vt_query(a)
@@ -225,8 +225,8 @@ def test_extend_batch_and_stop_at_first_failure(ctx):
 
 def test_prefix_sharing_aliases_the_same_physical_chunks(ctx):
     """Prefix match maps the SAME chunks into a second range: no new memory, writes through one alias are
-    visible through the other, chunks return to the pool only when the last mapping goes (paper Section 4.4
-    Prefix Record and Match; Section 4.2 pSet reference counts)."""
+    visible through the other, chunks return to the pool only when the last mapping goes (paper "vTensor Scheduler",
+    Prefix Record and Match; "vTensor Pool", pSet reference counts)."""
     src = vt.vt_reserve(ctx, 8, 128, vt.VT_BF16, 256)    # 32 rows per chunk
     vt.vt_extend(src, 80)
     s = vt.vt_query(src)

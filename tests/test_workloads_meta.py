@@ -72,7 +72,7 @@ def test_lengths_cover_the_inclusive_range():
 
 def test_region_arithmetic_matches_the_papers_example():
     """A 2 MB chunk of a 32-head, 128-dim fp16 K region holds 256 token rows, the initial allocation the
-    paper gives as its example next to a 4096-token virtual range (Section 4.2, vSet)."""
+    paper gives as its example next to a 4096-token virtual range ("vTensor Pool", vSet)."""
     g = golden()
     chunk = int(g["chunk_megabytes"]) * 1024 * 1024
     assert chunk == meta.CHUNK_BYTES
