@@ -168,7 +168,8 @@ typedef struct {
 
 /* Integer work decomposition of a decode call ("tape split").  Per KV head, the requests' cached tokens laid
  * end to end form a tape of total = sum_b len_b tokens, cut into segments of span_tokens tokens; one wavefront
- * owns one (segment, kv head, sub-group of at most 16 of the head's query heads).  With slots = the plan target
+ * owns one (segment, kv head, sub-group of at most 16 of the head's query heads; two such sub-groups of one kv head
+ * when the head has more than 16 query heads).  With slots = the plan target
  * (default 2048 wavefront slots) and U = n_kv_heads * ceil((n_q_heads / n_kv_heads) / 16):
  *   n_seg       = max(1, min(slots / U, ceil(total / 32)))
  *   span_tokens = round_up(ceil(total / n_seg), 32)

@@ -134,9 +134,12 @@ struct Piece {
   const char* vb;
 };
 
-template <int DT, int D>
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_kernel(
-    DecodeParams p) {
+// NB: blocks of 16 query heads one wavefront carries (1, or 2 for groups of more than 16 heads: the second block
+// reuses the tile's K rows in LDS and its transposed V registers, so the K/V head is read once for 32 heads; that
+// variant needs more than 256 registers and runs one wavefront per SIMD).
+template <int DT, int D, int NB>
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 2 : 1, NB == 1 ? 2 : 1))) void
+decode_kernel(DecodeParams p) {
   using T = Tile<D>;
   constexpr int CH = T::CH, TPL = T::TPL, NLK = T::NLK;
   constexpr int KK = D / 32;       // MFMA k-steps of the score product
@@ -198,12 +201,15 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   // A wavefront carries at most 16 query heads (the N dimension of the MFMA).  A group of more than 16 is cut into
   // sub-groups of 16 that each get a wavefront of their own and read the same K/V head (the four wavefronts of a
   // workgroup are neighbours in this numbering, so the repeated reads meet in the caches).
-  const unsigned units_per_seg = p.hkv * p.sub;
+  const unsigned wsub = (p.sub + NB - 1) / NB;            // wavefronts per (segment, kv head)
+  const unsigned units_per_seg = p.hkv * wsub;
   const int sidx = (int)(w_global / units_per_seg);
   const int gv = (int)(w_global - (unsigned)sidx * units_per_seg);
-  const int g = gv / (int)p.sub;                          // kv head
-  const int h0 = (gv - g * (int)p.sub) * 16;              // first query head of the sub-group inside the group
-  const int n_heads = min(16, (int)p.group - h0);         // query heads this wavefront carries
+  const int g = gv / (int)wsub;                           // kv head
+  const int h0 = (gv - g * (int)wsub) * 16 * NB;          // first query head of this wavefront inside the group
+  int n_heads[NB];                                        // query heads of each 16-head block this wavefront carries
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) n_heads[nb] = max(0, min(16, (int)p.group - h0 - 16 * nb));
   const int seg0 = sidx * seg_len;
   if (sidx >= (int)p.n_seg || seg0 >= total) return;
   const int seg1 = min(seg0 + seg_len, total);
@@ -238,21 +244,24 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
     make_piece(nxt, lo + 1);
   }
 
-  u32x4 qf[KK];
-  f32x4 acc[NM];
-  float m_run, l_run;
+  u32x4 qf[NB][KK];
+  f32x4 acc[NB][NM];
+  float m_run[NB], l_run[NB];
   // Q as the B operand: lane (head c16, slot j) holds d-chunk 4*kk + j of its head; heads >= group are zero.
   auto begin_piece = [&](const Piece& d) {
-    const char* qh = p.q + ((size_t)d.b * p.hq + (size_t)g * p.group + h0 + c16) * D * 2;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      u32x4 z = {0u, 0u, 0u, 0u};
-      qf[kk] = (c16 < n_heads) ? *(const u32x4*)(qh + (4 * kk + j) * 16) : z;
+    for (int nb = 0; nb < NB; ++nb) {
+      const char* qh = p.q + ((size_t)d.b * p.hq + (size_t)g * p.group + h0 + 16 * nb + c16) * D * 2;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        qf[nb][kk] = (c16 < n_heads[nb]) ? *(const u32x4*)(qh + (4 * kk + j) * 16) : z;
+      }
+#pragma unroll
+      for (int m = 0; m < NM; ++m) acc[nb][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+      m_run[nb] = -INFINITY;
+      l_run[nb] = 0.f;
     }
-#pragma unroll
-    for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-    m_run = -INFINITY;
-    l_run = 0.f;
   };
 
   auto load_tile = [&](T& t, const Piece& d, int tile) {
@@ -278,54 +287,57 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    f32x4 sc[2];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      sc[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const u32x4 kf = *(const u32x4*)(lds + (16 * hh + c16) * RSB + (4 * kk + j) * 16);
-        sc[hh] = Elem<DT>::mfma(kf, qf[kk], sc[hh]);
-      }
-    }
-    // Online softmax for head c16 over this lane's 8 tokens (4*j+i and 16+4*j+i) and, via two
-    // cross-lane exchanges, over all 32 tokens of the tile.
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = tile + (e & 3) + 4 * j + (e >> 2) * 16;
-      const float v = sc[e >> 2][e & 3] * p.scale_log2e;
-      x[e] = tok < t1 ? v : -INFINITY;
-    }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float pr[8], psum = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      pr[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
-      psum += pr[e];
-    }
-    l_run = l_run * alpha + psum;
-    const u32x4 pf = Elem<DT>::pack8(pr);
-    // V^T operand by in-lane transpose, then O^T += V^T P^T.
     u32x4 vt[8];
-    transpose8x8(t.v, vt);
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      u32x4 a;
-      if constexpr (D == 128) {
-        a = vt[m];
-      } else {
-        // D = 64: lanes c16 and c16+8 hold the same chunk; rows 0-7 take even columns, rows 8-15 odd ones.
+    for (int nb = 0; nb < NB; ++nb) {
+      f32x4 sc[2];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) a[w] = (c16 < 8) ? vt[2 * m][w] : vt[2 * m + 1][w];
+      for (int hh = 0; hh < 2; ++hh) {
+        sc[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const u32x4 kf = *(const u32x4*)(lds + (16 * hh + c16) * RSB + (4 * kk + j) * 16);
+          sc[hh] = Elem<DT>::mfma(kf, qf[nb][kk], sc[hh]);
+        }
       }
-      acc[m] *= alpha;
-      acc[m] = Elem<DT>::mfma(a, pf, acc[m]);
+      // Online softmax for head c16 over this lane's 8 tokens (4*j+i and 16+4*j+i) and, via two
+      // cross-lane exchanges, over all 32 tokens of the tile.
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int tok = tile + (e & 3) + 4 * j + (e >> 2) * 16;
+        const float v = sc[e >> 2][e & 3] * p.scale_log2e;
+        x[e] = tok < t1 ? v : -INFINITY;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[nb], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+      m_run[nb] = m_new;
+      float pr[8], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pr[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+        psum += pr[e];
+      }
+      l_run[nb] = l_run[nb] * alpha + psum;
+      const u32x4 pf = Elem<DT>::pack8(pr);
+      // V^T operand by in-lane transpose (once per tile, shared by the head blocks), then O^T += V^T P^T.
+      if (nb == 0) transpose8x8(t.v, vt);
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        u32x4 a;
+        if constexpr (D == 128) {
+          a = vt[m];
+        } else {
+          // D = 64: lanes c16 and c16+8 hold the same chunk; rows 0-7 take even columns, rows 8-15 odd ones.
+#pragma unroll
+          for (int w = 0; w < 4; ++w) a[w] = (c16 < 8) ? vt[2 * m][w] : vt[2 * m + 1][w];
+        }
+        acc[nb][m] *= alpha;
+        acc[nb][m] = Elem<DT>::mfma(a, pf, acc[nb][m]);
+      }
     }
   };
 
@@ -337,49 +349,52 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 
   };
 
   auto end_piece = [&](const Piece& d) {
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    if (c16 >= n_heads) return;
-    const size_t head = (size_t)g * p.group + h0 + c16;
-    if (d.count == 1) {
-      // The piece is the whole request: normalise and write the output row.
-      const float inv = 1.0f / l_run;
-      unsigned short* o = (unsigned short*)p.out + ((size_t)d.b * p.hq + head) * D;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 16);
+      l_tot += __shfl_xor(l_tot, 32);
+      if (c16 >= n_heads[nb]) continue;
+      const size_t head = (size_t)g * p.group + h0 + 16 * nb + c16;
+      if (d.count == 1) {
+        // The piece is the whole request: normalise and write the output row.
+        const float inv = 1.0f / l_tot;
+        unsigned short* o = (unsigned short*)p.out + ((size_t)d.b * p.hq + head) * D;
+        if constexpr (D == 128) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float r[8];
+#pragma unroll
+            for (int m = 0; m < 8; ++m) r[m] = acc[nb][m][i] * inv;
+            *(u32x4*)(o + 32 * j + 8 * i) = Elem<DT>::pack8(r);
+          }
+        } else {
+#pragma unroll
+          for (int m = 0; m < NM; ++m)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[d_of(m, i)] = Elem<DT>::cvt(acc[nb][m][i] * inv);
+        }
+        continue;
+      }
+      const size_t pidx = ((size_t)d.b * p.max_pieces + d.index) * p.hq + head;
+      float* pa = p.part_acc + pidx * D;
       if constexpr (D == 128) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float r[8];
-#pragma unroll
-          for (int m = 0; m < 8; ++m) r[m] = acc[m][i] * inv;
-          *(u32x4*)(o + 32 * j + 8 * i) = Elem<DT>::pack8(r);
+          f32x4 lo = {acc[nb][0][i], acc[nb][1][i], acc[nb][2][i], acc[nb][3][i]};
+          f32x4 hi = {acc[nb][4][i], acc[nb][5][i], acc[nb][6][i], acc[nb][7][i]};
+          *(f32x4*)(pa + 32 * j + 8 * i) = lo;
+          *(f32x4*)(pa + 32 * j + 8 * i + 4) = hi;
         }
       } else {
 #pragma unroll
         for (int m = 0; m < NM; ++m)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) o[d_of(m, i)] = Elem<DT>::cvt(acc[m][i] * inv);
+          for (int i = 0; i < 4; ++i) pa[d_of(m, i)] = acc[nb][m][i];
       }
-      return;
-    }
-    const size_t pidx = ((size_t)d.b * p.max_pieces + d.index) * p.hq + head;
-    float* pa = p.part_acc + pidx * D;
-    if constexpr (D == 128) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        f32x4 lo = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-        f32x4 hi = {acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
-        *(f32x4*)(pa + 32 * j + 8 * i) = lo;
-        *(f32x4*)(pa + 32 * j + 8 * i + 4) = hi;
+      if (j == 0) {
+        p.part_m[pidx] = m_run[nb];
+        p.part_l[pidx] = l_tot;
       }
-    } else {
-#pragma unroll
-      for (int m = 0; m < NM; ++m)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pa[d_of(m, i)] = acc[m][i];
-    }
-    if (j == 0) {
-      p.part_m[pidx] = m_run;
-      p.part_l[pidx] = l_run;
     }
   };
 
@@ -559,14 +574,19 @@ int launch_decode(vt_ctx* ctx, const vt_decode_args* a, const DecodePlan& plan, 
   p.n_seg = plan.n_seg;
   p.scale_log2e = a->scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
-  const uint64_t waves = (uint64_t)plan.n_seg * a->n_kv_heads * p.sub;
+  // Groups of more than 16 query heads: one wavefront carries two 16-head blocks of a kv head.
+  const uint32_t nb = p.sub > 1 ? 2 : 1;
+  const uint64_t waves = (uint64_t)plan.n_seg * a->n_kv_heads * ((p.sub + nb - 1) / nb);
   const uint32_t blocks = (uint32_t)((waves + kWaves - 1) / kWaves);
   const dim3 cgrid(p.hq, a->batch);
   const bool combine = plan.max_pieces > 1;
   if (allow_profile) prof_begin(ctx, 0, st);
 #define VT_LAUNCH(DT, DD)                                                                        \
   do {                                                                                           \
-    hipLaunchKernelGGL((decode_kernel<DT, DD>), dim3(blocks), dim3(64 * kWaves), 0, st, p);      \
+    if (nb == 1)                                                                                 \
+      hipLaunchKernelGGL((decode_kernel<DT, DD, 1>), dim3(blocks), dim3(64 * kWaves), 0, st, p); \
+    else                                                                                         \
+      hipLaunchKernelGGL((decode_kernel<DT, DD, 2>), dim3(blocks), dim3(64 * kWaves), 0, st, p); \
     if (allow_profile) prof_end(ctx, st);                                                        \
     if (combine && plan.max_pieces <= 4)                                                         \
       hipLaunchKernelGGL((decode_combine_kernel<DT, DD, 1>), cgrid, dim3(64), 0, st, p);         \
