@@ -167,16 +167,20 @@ __host__ __device__ inline uint32_t group_begin(uint32_t total, uint32_t n, uint
 }
 // Floats of one piece slot: 256 maxima, 256 sums, 256 x D accumulators.
 __host__ __device__ constexpr uint32_t piece_floats(int d) { return 512u + 256u * (uint32_t)d; }
-// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16*l (lds_addr uniform).
+// 16 bytes per lane from global memory straight into LDS: lane l lands at LDS address lds_base + LDS_OFF + 16*l
+// (lds_base uniform) and fetches from base + row_off + (chunk ^ XOR) (base uniform, the rest 32-bit lane values).
 // Written as assembly so that these loads are invisible to the compiler's wait-count bookkeeping: it would
 // otherwise guard operand reads of the tile buffers with waits for every outstanding load.  The kernel places
-// its own waits (wait_loads) and barriers.  The address is a uniform base plus a 32-bit lane offset.  (m0 is
-// written here; nothing else in this file uses it.)
-__device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_off), "s"(base), "s"(lds_addr)
-               : "memory");
+// its own waits (wait_loads) and barriers.  m0 (the LDS address; nothing else in this file uses it) must be
+// written one instruction before the load reads it: the lane offset is worked out in between.
+template <int LDS_OFF, int XOR>
+__device__ __forceinline__ void dma16(const char* base, uint32_t row_off, uint32_t chunk, uint32_t lds_base) {
+  static_assert(XOR >= 0 && XOR <= 64, "inline constant");
+  uint32_t t;
+  asm volatile("s_add_u32 m0, %3, %4\n\tv_xad_u32 %0, %1, %5, %2\n\tglobal_load_lds_dwordx4 %0, %6"
+               : "=&v"(t)
+               : "v"(chunk), "v"(row_off), "s"(lds_base), "n"(LDS_OFF), "n"(XOR), "s"(base)
+               : "memory", "scc");
 }
 // Accesses at device scope for data that workgroups on different XCDs hand to each other inside one launch (each
 // XCD has its own L2): the store goes through to memory, the load does not take the line from this XCD's L2.
@@ -293,11 +297,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
   constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
   constexpr int STG = 64 + 16;         // bytes of one output staging row: 32 values and a pad
-  // Four tile buffers (K tile, then V tile), separate arrays rather than one array indexed by the buffer number.
-  __shared__ __attribute__((aligned(1024))) char lds_t0[2 * TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_t1[2 * TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_t2[2 * TILEB];
-  __shared__ __attribute__((aligned(1024))) char lds_t3[2 * TILEB];
+  // Four tile buffers (K tile, then V tile each).
+  __shared__ __attribute__((aligned(1024))) char lds_tiles[4 * 2 * TILEB];
   // Output staging, one area per wavefront (the tile buffers are never free: the next piece's tiles are on their way).
   __shared__ __attribute__((aligned(16))) char lds_stage[4][64 * STG];
   __shared__ uint32_t s_pre[kMaxPrefillBatch + 1];
@@ -490,6 +491,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     r.jbase = 0;
     return r;
   };
+  // End of the run of fast tiles of one segment that holds tile s of the current piece (s + 1 when s is not such a
+  // tile): up to there, each tile lies 64 rows after its predecessor.
+  auto run_end_of = [&](int s) -> int {
+    const int nfast_item = cur.fastA + cur.fastB;
+    return s < cur.fastA ? min(cur.fastA, s1) : (s < min(nfast_item, s1) ? min(nfast_item, s1) : s + 1);
+  };
   // Looks up the three tiles that follow the current piece in the stream and parks them.
   auto park_ahead = [&]() {
     Piece nx = next_piece(cur);
@@ -539,6 +546,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     }
   };
   int lim[2];
+  int run_end = 0;  // end of the run of fast tiles (see run_end_of) that holds the tile the fast-tile code loads next
   u32x4 qf[2][KS];
   f32x16 acc[DB][2];
   float m_used[2], l_run[2];
@@ -549,31 +557,35 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // lands in row `row` at chunk position ld_pos and therefore fetches the chunk that the swizzle assigns to
   // that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).  Rows past the
   // end of the segment repeat its last row (they are masked later).  A tile's loads are issued a pair (one of
-  // K, one of V) at a time between the compute stages rather than back to back, and their lane offsets are
-  // recomputed from the lane number on every call (the asm hides the value from loop-invariant hoisting):
-  // keeping them live across the compute phases costs vector registers the hot loop needs.
-  auto issue_part = [&](auto part, const Tile& tl, char* tile_k, char* tile_v) {
+  // K, one of V) at a time between the compute stages rather than back to back.  Three values per lane stay in
+  // registers: the byte offset of its row in load 0 and its two swizzled chunk offsets there.  Load i is RPI*i rows
+  // further; RPI/RPL is 4 and the lane's row/RPL in load 0 is below 4 modulo CH, so the K swizzle of load i is
+  // that of load 0 with 4*i XORed in (64*i in bytes) and the V swizzle does not depend on i.  A tile buffer is the K
+  // tile followed by the V tile.
+  static_assert(RPI / RPL == 4 && (NLD * RPI / RPL) % CH == 0, "swizzle of load i from that of load 0");
+  const int ld_r = wave * NLD * RPI + lane / CH, ld_pos = lane % CH;
+  const uint32_t ld_row0 = (uint32_t)ld_r * row_bytes;
+  const uint32_t ld_chunk_k = (uint32_t)((ld_pos ^ ((ld_r / RPL) % CH)) * 16);
+  const uint32_t ld_chunk_k2 = ld_chunk_k ^ 128u;  // (loads 2 and 3: XORs with 128 and 192 = 128 ^ 64)
+  const uint32_t ld_chunk_v = (uint32_t)((ld_pos ^ (4 * ((ld_r / RPL) % (CH / 4)))) * 16);
+  auto issue_part = [&](auto part, const Tile& tl, char* tile_k) {
     constexpr int i = decltype(part)::value;
-    unsigned l = (unsigned)lane;
-    asm volatile("" : "+v"(l));
-    const int row = wave * NLD * RPI + i * RPI + (int)(l / CH), ld_pos = (int)(l % CH);
-    const uint32_t lk = (uint32_t)uni((int)lds_addr_of(tile_k) + (wave * NLD + i) * 1024);
-    const uint32_t lv = (uint32_t)uni((int)lds_addr_of(tile_v) + (wave * NLD + i) * 1024);
-    const uint32_t ro = __umul24((unsigned)min(row, tl.last_row), row_bytes);
-    dma16(tl.k, ro + (uint32_t)((ld_pos ^ ((row / RPL) % CH)) * 16), lk);
-    dma16(tl.v, ro + (uint32_t)((ld_pos ^ (4 * ((row / RPL) % (CH / 4)))) * 16), lv);
+    const uint32_t lb = (uint32_t)uni((int)lds_addr_of(tile_k) + wave * NLD * 1024);
+    const uint32_t ro = min(ld_row0 + (uint32_t)(i * RPI) * row_bytes, __umul24((unsigned)tl.last_row, row_bytes));
+    dma16<i * 1024, (i & 1) * 64>(tl.k, ro, i < 2 ? ld_chunk_k : ld_chunk_k2, lb);
+    dma16<TILEB + i * 1024, 0>(tl.v, ro, ld_chunk_v, lb);
   };
   static_assert(NLD == 2 || NLD == 4, "tile load split");
   const std::integral_constant<int, 0> part0;
   const std::integral_constant<int, 1> part1;
   const std::integral_constant<int, 2> part2;
   const std::integral_constant<int, 3> part3;
-  auto issue_tile = [&](const Tile& tl, char* tile_k, char* tile_v) {
-    issue_part(part0, tl, tile_k, tile_v);
-    issue_part(part1, tl, tile_k, tile_v);
+  auto issue_tile = [&](const Tile& tl, char* tile_k) {
+    issue_part(part0, tl, tile_k);
+    issue_part(part1, tl, tile_k);
     if constexpr (NLD > 2) {
-      issue_part(part2, tl, tile_k, tile_v);
-      issue_part(part3, tl, tile_k, tile_v);
+      issue_part(part2, tl, tile_k);
+      issue_part(part3, tl, tile_k);
     }
   };
 
@@ -700,12 +712,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     __builtin_amdgcn_s_barrier();
   };
   auto issue_before_sync = [&](const Tile& t2, char* gk) {
-    issue_part(part1, t2, gk, gk + TILEB);
-    if constexpr (NLD > 2) issue_part(part2, t2, gk, gk + TILEB);
+    issue_part(part1, t2, gk);
+    if constexpr (NLD > 2) issue_part(part2, t2, gk);
   };
   auto issue_after_sync = [&](const Tile& t2, const Tile& t3, char* gk, char* fk) {
-    if constexpr (NLD > 2) issue_part(part3, t2, gk, gk + TILEB);
-    issue_part(part0, t3, fk, fk + TILEB);
+    if constexpr (NLD > 2) issue_part(part3, t2, gk);
+    issue_part(part0, t3, fk);
   };
 
   // Fast tile: every (row, key) pair visible, reference maxima fixed.  The instruction order is fixed by hand:
@@ -741,13 +753,26 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       thr0 = min(lim[0] - cur.jbase, cur.last_row) - 4 * hi;
       thr1 = min(lim[1] - cur.jbase, cur.last_row) - 4 * hi;
     }
+    // Tile kt+3.  Inside a run of fast tiles of one segment it is 64 rows after tile kt+2; a full look-up otherwise.
+    // (Here rather than where stage F uses it: the look-up branches, and with a branch between them the compiler
+    // moves the weights of stages D and E down to their first use in F, off the slots they were given.)
+    Tile t3;
+    if (__builtin_expect(kt + 3 < run_end, 1)) {
+      t3.k = t2.k + (size_t)kBN * row_bytes;
+      t3.v = t2.v + (size_t)kBN * row_bytes;
+      t3.last_row = kBN - 1;
+      t3.jbase = 0;
+    } else {
+      t3 = tile_ahead(kt + 3);
+      run_end = run_end_of(kt + 3);
+    }
     // A
     zero(s0v[0]);
     static_for<0, KS>([&](auto i) {
       s0v[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0v[0]);
       k1[i] = read_k(i, ck, 1);
-      if constexpr (i == 0) issue_part(part1, t2, gk, gk + TILEB);
-      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk, gk + TILEB);
+      if constexpr (i == 0) issue_part(part1, t2, gk);
+      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk);
       __builtin_amdgcn_sched_barrier(0);
     });
     // B
@@ -790,21 +815,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     l_run[1] += ps;
     sync_next();
     // F
-    const Tile t3 = tile_ahead(kt + 3);
     static_for<0, NPV>([&](auto i) {
       pv_mfma(i, v1h, p1);
       if constexpr (i < KS) k0[i] = read_k(i, nk, 0);
-      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk, gk + TILEB);
-      if constexpr (i == NPV / 2) issue_part(part0, t3, fk, fk + TILEB);
+      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk);
+      if constexpr (i == NPV / 2) issue_part(part0, t3, fk);
       __builtin_amdgcn_sched_barrier(0);
     });
     t2 = t3;
   };
 
-  auto buf_of = [&](int i) -> char* {
-    const int m = i & 3;
-    return m == 0 ? lds_t0 : (m == 1 ? lds_t1 : (m == 2 ? lds_t2 : lds_t3));
-  };
+  auto buf_of = [&](int i) -> char* { return lds_tiles + (i & 3) * (2 * TILEB); };
 
   // Generic tile: masked (ragged end of a segment, causal diagonal), classic online softmax (reference maxima
   // follow the data, accumulators rescaled when a maximum moves by more than kTau).  Row r of the tile is
@@ -938,11 +959,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       l_run[0] = l_run[1] = 0.f;
 
       Tile t2;
+      run_end = run_end_of(s0 + 2);
       if (!primed) {
-        issue_tile(tile_ahead(s0), buf_of(gt), buf_of(gt) + TILEB);
-        issue_tile(tile_ahead(s0 + 1), buf_of(gt + 1), buf_of(gt + 1) + TILEB);
+        issue_tile(tile_ahead(s0), buf_of(gt));
+        issue_tile(tile_ahead(s0 + 1), buf_of(gt + 1));
         t2 = tile_ahead(s0 + 2);
-        issue_part(part0, t2, buf_of(gt + 2), buf_of(gt + 2) + TILEB);
+        issue_part(part0, t2, buf_of(gt + 2));
         wait_loads(std::integral_constant<int, VM + 2>{});
         __builtin_amdgcn_s_barrier();
         primed = true;
