@@ -231,7 +231,10 @@ typedef struct {
 /* Prefix-prefill attention: new token i of request b (absolute position P_b + i) attends keys
  * 0 .. P_b + i of concat(cached prefix, new tokens): the whole prefix plus the new tokens causally.
  * FlashAttention-style tiling on MFMA with fp32 accumulation.  Paper: "Prefix Cache",
- * "Prefix-prefilling Kernel Evaluation".  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024. */
+ * "Prefix-prefilling Kernel Evaluation".  Errors as vt_attn_decode; head_dim must be 128 or 64, batch <= 1024.
+ * With head_dim 128 the kernel runs as eight wavefronts of 32 query rows (two per SIMD); a context created while the
+ * environment holds VT_PREFILL_WIDE=1 runs it as four wavefronts of 64 rows instead (the shape head_dim 64 always
+ * uses) - same results up to rounding order, kept so that the two can be timed against each other. */
 int vt_attn_prefix_prefill(vt_ctx* ctx, const vt_prefill_args* args, void* stream);
 
 /* Integer work decomposition of a prefix-prefill call.  An item is (request, kv head, token tile of
@@ -274,7 +277,7 @@ int vt_workspace_reserve(vt_ctx* ctx, uint64_t bytes);
 /* ---- misc ------------------------------------------------------------------------------------ */
 
 /* Kernel timing for benchmarks.  While enabled, vt_attn_decode brackets its split-pass kernel (which = 0)
- * and vt_attn_prefix_prefill its two kernels (which = 1) with HIP events recorded on the caller's stream.
+ * and vt_attn_prefix_prefill its kernel (which = 1) with HIP events recorded on the caller's stream.
  * vt_profile_collect waits for the events recorded so far, returns their summed elapsed time and count
  * for `which`, and forgets them.  At most 4096 launches are kept between two collects. */
 int vt_profile_enable(vt_ctx* ctx, int on);

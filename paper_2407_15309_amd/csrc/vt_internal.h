@@ -80,6 +80,7 @@ struct vt_ctx {
   void* arrivals;             // device, kMaxPrefillGroups 8-byte words, zero at creation: arrival counts of the
                               // prefix-prefill items shared between workgroups, tagged with the launch number
   uint64_t prefill_launches;  // prefix-prefill launches on this context so far
+  bool prefill_wide;          // VT_PREFILL_WIDE=1 when the context was created: head_dim 128 runs the 4-wavefront kernel
   int n_cus;
   bool profile;
   std::vector<vt::ProfEvent> prof;

@@ -13,6 +13,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -205,6 +206,10 @@ int make_ctx(vt_ctx** out, Backend* be, int device, uint64_t chunk_bytes, uint64
   c->ws_bytes = 0;
   c->arrivals = nullptr;
   c->prefill_launches = 0;
+  {
+    const char* wide = std::getenv("VT_PREFILL_WIDE");
+    c->prefill_wide = wide && wide[0] == '1';
+  }
   c->n_cus = 256;
   c->profile = false;
   *out = c;

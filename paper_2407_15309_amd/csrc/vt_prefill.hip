@@ -7,10 +7,12 @@
 // "vTensor"); the new tokens' rows come from k_new / v_new, or from the region itself when the caller
 // has already appended them.
 //
-// Tiling: a workgroup of 4 wavefronts computes 256 query rows of one (request, kv head) at a time: the G
-// query heads of the group for 256/G consecutive new tokens, so one K/V tile read serves every head of the
-// group.  It sweeps the visible keys in tiles of 64.  Per tile, with v_mfma_f32_32x32x16:
-//   S^T[key, row]  = K_tile[64 x D] * Q^T[D x 64 rows per wavefront]     (A = K from LDS, B = Q in registers)
+// Tiling: a workgroup computes 256 query rows of one (request, kv head) at a time: the G query heads of the
+// group for 256/G consecutive new tokens, so one K/V tile read serves every head of the group.  It sweeps the
+// visible keys in tiles of 64.  The rows are split over eight wavefronts of 32 rows (head_dim 128: two wavefronts
+// per SIMD, 256 registers each) or four wavefronts of 64 rows (one per SIMD, up to 512 registers).  Per tile, with
+// v_mfma_f32_32x32x16:
+//   S^T[key, row]  = K_tile[64 x D] * Q^T[D x rows of the wavefront]      (A = K from LDS, B = Q in registers)
 //   O^T[d, row]   += V_tile^T[D x 64 keys] * P^T[64 keys x rows]         (A = V^T from LDS, B = P in registers)
 // Keys run along the rows of S^T, so a softmax reduction over keys is 16 in-lane values plus one
 // cross-lane exchange, and the result registers of the first product are, value for value, the B operand
@@ -20,10 +22,10 @@
 // tile), form one sequence; workgroup w of n owns the w-th n-th of it.  A workgroup therefore computes some
 // whole items and at most two pieces of items it shares with its neighbours.  A whole item is normalised
 // and written out at once; a piece leaves its running maxima, sums and unnormalised accumulators in a
-// workspace slot, and a second kernel merges the pieces of every shared item.  Every workgroup gets the same
-// amount of work (in cost units: tiles plus a fixed share per item) whatever the mix of lengths, and a call with
-// fewer items than compute units still fills the chip.  Runs of consecutive shares go to the same XCD, whose L2
-// then serves part of the repeated sweeps over one K/V range.
+// workspace slot, and the workgroup that finishes the last piece of a shared item merges them.  Every
+// workgroup gets the same amount of work (in cost units: tiles plus a fixed share per item) whatever the mix of
+// lengths, and a call with fewer items than compute units still fills the chip.  Runs of consecutive shares go
+// to the same XCD, whose L2 then serves part of the repeated sweeps over one K/V range.
 //
 // Data movement: K and V tiles go from global memory straight into LDS (global_load_lds, 16 B per lane, no
 // registers), four tile buffers, one workgroup barrier per tile.  Both tiles keep their natural [key][d]
@@ -251,9 +253,10 @@ __device__ __forceinline__ ItemPos locate(const PrefillParams& p, const uint32_t
   r.shape = sh;
   return r;
 }
-__device__ __forceinline__ void build_prefix(const PrefillParams& p, uint32_t* s_pre, int tid, bool split) {
+__device__ __forceinline__ void build_prefix(const PrefillParams& p, uint32_t* s_pre, int tid, int n_threads,
+                                             bool split) {
   const int B = (int)p.batch;
-  for (int r = tid; r < B; r += 256)
+  for (int r = tid; r < B; r += n_threads)
     s_pre[r + 1] = request_cost(p.plens[r], p.cu[r + 1] - p.cu[r], (int)p.tb, split) * p.hkv;
   __syncthreads();
   if (tid == 0) {
@@ -286,8 +289,15 @@ struct Piece {
   const char *kc, *vc, *kn, *vn;  // row 0 of segment A (region) and of segment B (k_new / v_new), at this kv head
 };
 
-template <int DT, int D>
-__global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
+// RB: 32-row blocks of query rows per wavefront.  RB = 2: four wavefronts of 64 rows, one per SIMD, each with up to 512
+// registers per lane.  RB = 1: eight wavefronts of 32 rows, two per SIMD with 256 registers each - every K and V operand
+// read then feeds one MFMA instead of two (twice the LDS traffic), but while one wavefront of a SIMD waits for LDS or
+// works on its weights the other one's MFMAs run.
+template <int DT, int D, int RB>
+__global__ __launch_bounds__(64 * (8 / RB)) void prefill_kernel(PrefillParams p) {
+  constexpr int NW = 8 / RB;           // wavefronts
+  constexpr int NT = 64 * NW;          // threads
+  constexpr int WR = 32 * RB;          // query rows per wavefront
   constexpr int CH = D / 8;            // 16-byte chunks per head row
   constexpr int KS = D / 16;           // k-steps of the score product
   constexpr int DB = D / 32;           // 32-row d blocks of the value product
@@ -295,12 +305,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   constexpr int RPL = 256 / ROWB;      // rows per 256-byte LDS bank line
   constexpr int RPI = 64 / CH;         // rows filled by one wavefront-wide load
   constexpr int TILEB = kBN * ROWB;    // bytes of one K (or V) tile
-  constexpr int NLD = kBN / RPI / 4;   // loads per wavefront, tile and tensor
+  constexpr int NLD = kBN / RPI / NW;  // loads per wavefront, tile and tensor
   constexpr int STG = 64 + 16;         // bytes of one output staging row: 32 values and a pad
   // Four tile buffers (K tile, then V tile each).
   __shared__ __attribute__((aligned(1024))) char lds_tiles[4 * 2 * TILEB];
   // Output staging, one area per wavefront (the tile buffers are never free: the next piece's tiles are on their way).
-  __shared__ __attribute__((aligned(16))) char lds_stage[4][64 * STG];
+  __shared__ __attribute__((aligned(16))) char lds_stage[NW][WR * STG];
   __shared__ uint32_t s_pre[kMaxPrefillBatch + 1];
   // Lengths and region addresses of the first few requests this workgroup works on, fetched once: a piece then
   // starts without a round trip to memory for them.
@@ -310,8 +320,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   __shared__ const char* s_wV[kWin];
   // Per wavefront: the three tiles that follow the current piece in this workgroup's tile stream (address of K row
   // 0, of V row 0, last row), written when the piece starts and read when the loads run past its end.
-  __shared__ int s_ahead[4][3][6];
-  __shared__ int s_vote[4];
+  __shared__ int s_ahead[NW][3][6];
+  __shared__ int s_vote[NW];
   __shared__ unsigned s_arrived;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -321,7 +331,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const bool split_src = p.k_new != nullptr;
   const uint32_t row_bytes = p.hkv * D * 2;
 
-  build_prefix(p, s_pre, tid, split_src);
+  build_prefix(p, s_pre, tid, NT, split_src);
   // Which group of the plan this workgroup is.  Workgroups are handed to the 8 XCDs in turn (workgroup i runs on
   // XCD i mod 8), and neighbouring groups sweep the same K/V rows (consecutive token tiles of one request and KV
   // head) at about the same time: give each XCD a run of consecutive groups, so that its L2 serves the re-reads.
@@ -531,8 +541,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   auto load_q = [&](const Piece& pc, u32x4 (*q)[KS]) {
     const int tok0 = pc.t * tb, nt = min(tb, pc.N - tok0);
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      const int r = wave * 64 + cb * 32 + col;
+    for (int cb = 0; cb < RB; ++cb) {
+      const int r = wave * WR + cb * 32 + col;
       const int t = r / G, q_head = r - t * G;
       const int q_tok = min(t, nt - 1);
       const unsigned keep = t < nt ? 0xffffffffu : 0u;
@@ -545,11 +555,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       }
     }
   };
-  int lim[2];
+  int lim[RB];
   int run_end = 0;  // end of the run of fast tiles (see run_end_of) that holds the tile the fast-tile code loads next
-  u32x4 qf[2][KS];
-  f32x16 acc[DB][2];
-  float m_used[2], l_run[2];
+  u32x4 qf[RB][KS];
+  f32x16 acc[DB][RB];
+  float m_used[RB], l_run[RB];
   bool wave_idle;
   load_q(cur, qf);
 
@@ -557,21 +567,24 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // lands in row `row` at chunk position ld_pos and therefore fetches the chunk that the swizzle assigns to
   // that position.  K rows are swizzled with (row/RPL) % CH, V rows with 4*((row/RPL) % (CH/4)).  Rows past the
   // end of the segment repeat its last row (they are masked later).  A tile's loads are issued a pair (one of
-  // K, one of V) at a time between the compute stages rather than back to back.  Three values per lane stay in
-  // registers: the byte offset of its row in load 0 and its two swizzled chunk offsets there.  Load i is RPI*i rows
-  // further; RPI/RPL is 4 and the lane's row/RPL in load 0 is below 4 modulo CH, so the K swizzle of load i is
+  // K, one of V) at a time between the compute stages rather than back to back.  A few values per lane stay in
+  // registers: the byte offset of its row in every load and its swizzled chunk offsets in load 0.  Load i is RPI*i rows
+  // further; RPI/RPL is 4 and the lane's row/RPL in load 0 is below 4 modulo 4*NLD, so the K swizzle of load i is
   // that of load 0 with 4*i XORed in (64*i in bytes) and the V swizzle does not depend on i.  A tile buffer is the K
   // tile followed by the V tile.
-  static_assert(RPI / RPL == 4 && (NLD * RPI / RPL) % CH == 0, "swizzle of load i from that of load 0");
+  static_assert(RPI / RPL == 4 && 64 / CH / RPL == 4 && (4 * NLD) <= CH, "swizzle of load i from that of load 0");
   const int ld_r = wave * NLD * RPI + lane / CH, ld_pos = lane % CH;
-  const uint32_t ld_row0 = (uint32_t)ld_r * row_bytes;
+  uint32_t ld_row[NLD];  // byte offset of the lane's row in load i
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) ld_row[i] = (uint32_t)(ld_r + i * RPI) * row_bytes;
   const uint32_t ld_chunk_k = (uint32_t)((ld_pos ^ ((ld_r / RPL) % CH)) * 16);
   const uint32_t ld_chunk_k2 = ld_chunk_k ^ 128u;  // (loads 2 and 3: XORs with 128 and 192 = 128 ^ 64)
   const uint32_t ld_chunk_v = (uint32_t)((ld_pos ^ (4 * ((ld_r / RPL) % (CH / 4)))) * 16);
   auto issue_part = [&](auto part, const Tile& tl, char* tile_k) {
     constexpr int i = decltype(part)::value;
     const uint32_t lb = (uint32_t)uni((int)lds_addr_of(tile_k) + wave * NLD * 1024);
-    const uint32_t ro = min(ld_row0 + (uint32_t)(i * RPI) * row_bytes, __umul24((unsigned)tl.last_row, row_bytes));
+    const uint32_t row_i = ld_row[i < NLD ? i : 0], row_last = __umul24((unsigned)tl.last_row, row_bytes);
+    const uint32_t ro = row_i < row_last ? row_i : row_last;
     dma16<i * 1024, (i & 1) * 64>(tl.k, ro, i < 2 ? ld_chunk_k : ld_chunk_k2, lb);
     dma16<TILEB + i * 1024, 0>(tl.v, ro, ld_chunk_v, lb);
   };
@@ -601,6 +614,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   const int v_within = 8 * (vi & 1);
   const float c = p.scale_log2e;
 
+  // In a run of fast tiles the K operand reads go through one LDS address per k-step that follows the tile buffers:
+  // k_at[ks] is the lane's address for key block 0 of the current tile (block 1 is a constant further).
+  uint32_t k_at[KS];
+  auto lds_read16 = [](uint32_t addr) -> u32x4 {
+    return *(const __attribute__((address_space(3))) u32x4*)addr;
+  };
   auto read_k = [&](auto ksc, const char* tk, int kb) -> u32x4 {
     constexpr int ks = decltype(ksc)::value;
     return *(const u32x4*)(tk + (32 * kb + col) * ROWB + (((2 * ks + hi) ^ kswz) * 16));
@@ -616,11 +635,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     return __builtin_bit_cast(u32x2,
                               __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a));
   };
-  // MFMA i of the value product of one 32-key block: operand i/2, query column block i%2.
-  constexpr int NPV = 4 * DB;  // MFMAs of one value product; also the transposing reads of one V block
+  // MFMA i of the value product of one 32-key block: operand i/RB, query column block i%RB.
+  constexpr int NVR = 4 * DB;       // transposing reads of one V block
+  constexpr int NPV = 2 * DB * RB;  // MFMAs of one value product
   auto pv_mfma = [&](auto ic, const u32x2* vh, u32x4 (*pf)[2]) {
     constexpr int i = decltype(ic)::value;
-    constexpr int m = i / 2, cb = i % 2, db = m / 2, s2 = m % 2;
+    constexpr int m = i / RB, cb = i % RB, db = m / 2, s2 = m % 2;
     u32x4 f;
     f[0] = vh[2 * m][0];
     f[1] = vh[2 * m][1];
@@ -632,14 +652,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) x[i] = 0.f;
   };
-  // S^T block (32 keys x 64 rows) = K Q^T.
+  // S^T block (32 keys x the wavefront's rows) = K Q^T.
   auto scores = [&](const char* tk, int kb, f32x16* s) {
-    zero(s[0]);
-    zero(s[1]);
+#pragma unroll
+    for (int cb = 0; cb < RB; ++cb) zero(s[cb]);
     static_for<0, KS>([&](auto ks) {
       const u32x4 kf = read_k(ks, tk, kb);
-      s[0] = PElem<DT>::mfma(kf, qf[0][ks], s[0]);
-      s[1] = PElem<DT>::mfma(kf, qf[1][ks], s[1]);
+#pragma unroll
+      for (int cb = 0; cb < RB; ++cb) s[cb] = PElem<DT>::mfma(kf, qf[cb][ks], s[cb]);
     });
   };
   // One of the nine steps that turn a 32-key x 32-row score block (16 values per lane) into softmax weights
@@ -669,7 +689,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   };
   auto weights = [&](const f32x16* s, u32x4 (*pf)[2]) {
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < RB; ++cb) {
       float pr[16], ps = 0.f;
       // (a row that has seen no key yet - possible when a piece starts on the causal diagonal - has no maximum;
       // its scores are all -inf and must give weight 0, not exp2(-inf + inf))
@@ -681,7 +701,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // Column maxima of a score block (over the lane's 16 keys and its partner half), in exp2 units.
   auto block_max = [&](const f32x16* s, float* tmax) {
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < RB; ++cb) {
       float t = fmaxf(s[cb][0], s[cb][1]);
 #pragma unroll
       for (int i = 2; i < 16; i += 2) t = fmaxf(t, fmaxf(s[cb][i], s[cb][i + 1]));
@@ -691,8 +711,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 
   // Waits until at most `n` of this wavefront's global-to-LDS loads are outstanding.
   auto wait_loads = [](auto n) {
-    constexpr int NW = decltype(n)::value;
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (NW & 15) | ((NW >> 4) << 14));
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
   };
   constexpr int VM = 2 * NLD;  // global-to-LDS loads per wavefront and tile
   // Tile pipeline.  The workgroup's tiles form one stream; the tile at stream position i lives in buffer i % 4.
@@ -736,93 +756,180 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // ck: this tile's buffer (K, then V); nk: the next tile's; gk: buffer of tile kt+2; fk: buffer of tile kt+3.
   // k0 holds K block 0 of this tile on entry and of the next tile on exit; t2 describes tile kt+2 on entry and
   // tile kt+3 (the next tile's kt+2) on exit.
-  static_assert(NPV == 2 * KS, "V reads are spread one per slot over two score stages");
+  static_assert(RB == 1 || NPV == 2 * KS, "V reads are spread one per slot over two score stages");
   auto fast_tile = [&](auto masked, int kt, const char* ck, const char* nk, char* gk, char* fk, u32x4* k0, Tile& t2) {
-    f32x16 s0v[2], s1v[2];
-    u32x4 p0[2][2], p1[2][2];
-    u32x4 k1[KS];
-    u32x2 v0h[NPV], v1h[NPV];
-    float pr[16], ps;
-    const float nm0 = -m_used[0], nm1 = -m_used[1];
-    const char* cv = ck + TILEB;
-    // masked variant: rows of the tile the two query rows of the lane see, as offsets from the lane's first row
-    // of key block 0 (block 1 is 32 further)
-    int thr0 = 0, thr1 = 0;
-    if constexpr (decltype(masked)::value) {
-      const Tile cur = tile_of(kt);
-      thr0 = min(lim[0] - cur.jbase, cur.last_row) - 4 * hi;
-      thr1 = min(lim[1] - cur.jbase, cur.last_row) - 4 * hi;
-    }
-    // Tile kt+3.  Inside a run of fast tiles of one segment it is 64 rows after tile kt+2; a full look-up otherwise.
-    // (Here rather than where stage F uses it: the look-up branches, and with a branch between them the compiler
-    // moves the weights of stages D and E down to their first use in F, off the slots they were given.)
-    Tile t3;
-    if (__builtin_expect(kt + 3 < run_end, 1)) {
-      t3.k = t2.k + (size_t)kBN * row_bytes;
-      t3.v = t2.v + (size_t)kBN * row_bytes;
-      t3.last_row = kBN - 1;
-      t3.jbase = 0;
+    if constexpr (RB == 2) {
+      f32x16 s0v[2], s1v[2];
+      u32x4 p0[2][2], p1[2][2];
+      u32x4 k1[KS];
+      u32x2 v0h[NPV], v1h[NPV];
+      float pr[16];
+      const float nm0 = -m_used[0], nm1 = -m_used[1];
+      const char* cv = ck + TILEB;
+      const uint32_t k_step = (uint32_t)uni((int)(lds_addr_of(nk) - lds_addr_of(ck)));
+      // masked variant: rows of the tile the two query rows of the lane see, as offsets from the lane's first row
+      // of key block 0 (block 1 is 32 further)
+      int thr0 = 0, thr1 = 0;
+      if constexpr (decltype(masked)::value) {
+        const Tile cur = tile_of(kt);
+        thr0 = min(lim[0] - cur.jbase, cur.last_row) - 4 * hi;
+        thr1 = min(lim[1] - cur.jbase, cur.last_row) - 4 * hi;
+      }
+      // Tile kt+3.  Inside a run of fast tiles of one segment it is 64 rows after tile kt+2; a full look-up otherwise.
+      // (Here rather than where stage F uses it: the look-up branches, and with a branch between them the compiler
+      // moves the weights of stages D and E down to their first use in F, off the slots they were given.)
+      Tile t3;
+      if (__builtin_expect(kt + 3 < run_end, 1)) {
+        t3.k = t2.k + (size_t)kBN * row_bytes;
+        t3.v = t2.v + (size_t)kBN * row_bytes;
+        t3.last_row = kBN - 1;
+        t3.jbase = 0;
+      } else {
+        t3 = tile_ahead(kt + 3);
+        run_end = run_end_of(kt + 3);
+      }
+      // A
+      zero(s0v[0]);
+      static_for<0, KS>([&](auto i) {
+        s0v[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0v[0]);
+        k1[i] = lds_read16(k_at[i] + 32 * ROWB);
+        if constexpr (i == 0) issue_part(part1, t2, gk);
+        if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // B
+      zero(s0v[1]);
+      static_for<0, KS>([&](auto i) {
+        s0v[1] = PElem<DT>::mfma(k0[i], qf[1][i], s0v[1]);
+        static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[0], nm0, pr, p0[0], l_run[0], masked, thr0); });
+        v0h[i] = read_v(i, cv, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // C
+      zero(s1v[0]);
+      static_for<0, KS>([&](auto i) {
+        s1v[0] = PElem<DT>::mfma(k1[i], qf[0][i], s1v[0]);
+        static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[1], nm1, pr, p0[1], l_run[1], masked, thr1); });
+        v0h[KS + i] = read_v(std::integral_constant<int, KS + i>{}, cv, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // D
+      zero(s1v[1]);
+      static_for<0, KS>([&](auto i) {
+        s1v[1] = PElem<DT>::mfma(k1[i], qf[1][i], s1v[1]);
+        static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s1v[0], nm0, pr, p1[0], l_run[0], masked, thr0 - 32); });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // E
+      static_for<0, NPV>([&](auto i) {
+        pv_mfma(i, v0h, p0);
+        static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1v[1], nm1, pr, p1[1], l_run[1], masked, thr1 - 32); });
+        v1h[i] = read_v(i, cv, 1);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      sync_next();
+      // F
+      static_for<0, NPV>([&](auto i) {
+        pv_mfma(i, v1h, p1);
+        if constexpr (i < KS) {
+          k_at[i] += k_step;
+          k0[i] = lds_read16(k_at[i]);
+        }
+        if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk);
+        if constexpr (i == NPV / 2) issue_part(part0, t3, fk);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      t2 = t3;
     } else {
-      t3 = tile_ahead(kt + 3);
-      run_end = run_end_of(kt + 3);
+      // Two wavefronts per SIMD, 32 rows each: four stages of eight slots, the same slot discipline.  What one
+      // wavefront's slots leave idle (waits for LDS, the barrier) the other wavefront of the SIMD fills, so the
+      // operand reads run only two slots ahead of their MFMA (a wavefront has 256 registers here):
+      //   A  S(block 0)                    | issues a load of tile kt+2
+      //   B  S(block 1)                    | weights of A's scores
+      //   C  O += V(block 0) P(block 0)    | weights of B's scores
+      //   -- synchronisation point --
+      //   D  O += V(block 1) P(block 1)    | issues a load of tile kt+3
+      // Operands in the order the 32 slots consume them: K block 0 (8 reads), K block 1 (8), V block 0 (8 pairs of
+      // transposing reads), V block 1 (8 pairs), then K block 0 of the next tile: slot n issues the read of slot n+2.
+      // k0[0] and k0[1] hold the first two operands on entry and those of the next tile on exit; k_at[j] moves on to
+      // the next tile's buffer right after its last use in this one.
+      static_assert(RB == 2 || (NLD == 2 && NPV == KS && NVR == 2 * KS), "slot plan of the 32-row tile");
+      f32x16 s0v, s1v;
+      u32x4 p0[1][2], p1[1][2];
+      u32x4 k1[KS];
+      u32x2 v0h[NVR], v1h[NVR];
+      float pr[16];
+      const float nm0 = -m_used[0];
+      const char* cv = ck + TILEB;
+      const uint32_t k_step = (uint32_t)uni((int)(lds_addr_of(nk) - lds_addr_of(ck)));
+      int thr0 = 0;
+      if constexpr (decltype(masked)::value) {
+        const Tile cur = tile_of(kt);
+        thr0 = min(lim[0] - cur.jbase, cur.last_row) - 4 * hi;
+      }
+      Tile t3;
+      if (__builtin_expect(kt + 3 < run_end, 1)) {
+        t3.k = t2.k + (size_t)kBN * row_bytes;
+        t3.v = t2.v + (size_t)kBN * row_bytes;
+        t3.last_row = kBN - 1;
+        t3.jbase = 0;
+      } else {
+        t3 = tile_ahead(kt + 3);
+        run_end = run_end_of(kt + 3);
+      }
+      // the read that slot n of the tile issues (n = 0 .. 31)
+      auto ahead = [&](auto nc) {
+        constexpr int n = decltype(nc)::value + 2;  // the slot it is for
+        if constexpr (n < KS) {
+          k0[n] = lds_read16(k_at[n]);
+        } else if constexpr (n < 2 * KS) {
+          k1[n - KS] = lds_read16(k_at[n - KS] + 32 * ROWB);
+          k_at[n - KS] += k_step;
+        } else if constexpr (n < 3 * KS) {
+          constexpr int m = n - 2 * KS;
+          v0h[2 * m] = read_v(std::integral_constant<int, 2 * m>{}, cv, 0);
+          v0h[2 * m + 1] = read_v(std::integral_constant<int, 2 * m + 1>{}, cv, 0);
+        } else if constexpr (n < 4 * KS) {
+          constexpr int m = n - 3 * KS;
+          v1h[2 * m] = read_v(std::integral_constant<int, 2 * m>{}, cv, 1);
+          v1h[2 * m + 1] = read_v(std::integral_constant<int, 2 * m + 1>{}, cv, 1);
+        } else {
+          k0[n - 4 * KS] = lds_read16(k_at[n - 4 * KS]);
+        }
+      };
+      // A
+      zero(s0v);
+      static_for<0, KS>([&](auto i) {
+        s0v = PElem<DT>::mfma(k0[i], qf[0][i], s0v);
+        ahead(i);
+        if constexpr (i == 0) issue_part(part1, t2, gk);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // B
+      zero(s1v);
+      static_for<0, KS>([&](auto i) {
+        s1v = PElem<DT>::mfma(k1[i], qf[0][i], s1v);
+        static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v, nm0, pr, p0[0], l_run[0], masked, thr0); });
+        ahead(std::integral_constant<int, KS + i>{});
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // C
+      static_for<0, NPV>([&](auto i) {
+        pv_mfma(i, v0h, p0);
+        static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1v, nm0, pr, p1[0], l_run[0], masked, thr0 - 32); });
+        ahead(std::integral_constant<int, 2 * KS + i>{});
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      sync_next();
+      // D
+      static_for<0, NPV>([&](auto i) {
+        pv_mfma(i, v1h, p1);
+        ahead(std::integral_constant<int, 3 * KS + i>{});
+        if constexpr (i == NPV / 2) issue_part(part0, t3, fk);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      t2 = t3;
     }
-    // A
-    zero(s0v[0]);
-    static_for<0, KS>([&](auto i) {
-      s0v[0] = PElem<DT>::mfma(k0[i], qf[0][i], s0v[0]);
-      k1[i] = read_k(i, ck, 1);
-      if constexpr (i == 0) issue_part(part1, t2, gk);
-      if constexpr (i == KS / 2 && NLD > 2) issue_part(part2, t2, gk);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // B
-    zero(s0v[1]);
-    ps = 0.f;
-    static_for<0, KS>([&](auto i) {
-      s0v[1] = PElem<DT>::mfma(k0[i], qf[1][i], s0v[1]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[0], nm0, pr, p0[0], ps, masked, thr0); });
-      v0h[i] = read_v(i, cv, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    l_run[0] += ps;
-    // C
-    zero(s1v[0]);
-    ps = 0.f;
-    static_for<0, KS>([&](auto i) {
-      s1v[0] = PElem<DT>::mfma(k1[i], qf[0][i], s1v[0]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s0v[1], nm1, pr, p0[1], ps, masked, thr1); });
-      v0h[KS + i] = read_v(std::integral_constant<int, KS + i>{}, cv, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    l_run[1] += ps;
-    // D
-    zero(s1v[1]);
-    ps = 0.f;
-    static_for<0, KS>([&](auto i) {
-      s1v[1] = PElem<DT>::mfma(k1[i], qf[1][i], s1v[1]);
-      static_for<i * 9 / KS, (i + 1) * 9 / KS>([&](auto j) { weight_step(j, s1v[0], nm0, pr, p1[0], ps, masked, thr0 - 32); });
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    l_run[0] += ps;
-    // E
-    ps = 0.f;
-    static_for<0, NPV>([&](auto i) {
-      pv_mfma(i, v0h, p0);
-      static_for<i * 9 / NPV, (i + 1) * 9 / NPV>([&](auto j) { weight_step(j, s1v[1], nm1, pr, p1[1], ps, masked, thr1 - 32); });
-      v1h[i] = read_v(i, cv, 1);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    l_run[1] += ps;
-    sync_next();
-    // F
-    static_for<0, NPV>([&](auto i) {
-      pv_mfma(i, v1h, p1);
-      if constexpr (i < KS) k0[i] = read_k(i, nk, 0);
-      if constexpr (i == 0 && NLD > 2) issue_part(part3, t2, gk);
-      if constexpr (i == NPV / 2) issue_part(part0, t3, fk);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    t2 = t3;
   };
 
   auto buf_of = [&](int i) -> char* { return lds_tiles + (i & 3) * (2 * TILEB); };
@@ -832,27 +939,34 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
   // visible to a query row iff it exists and its position jbase + r does not exceed the row's limit.
   auto generic_tile = [&](const char* tk, const Tile& tl) {
     const char* tv = tk + TILEB;
-    const int vis0 = min(lim[0] - tl.jbase, tl.last_row), vis1 = min(lim[1] - tl.jbase, tl.last_row);
+    int vis[RB];
+#pragma unroll
+    for (int cb = 0; cb < RB; ++cb) vis[cb] = min(lim[cb] - tl.jbase, tl.last_row);
 #pragma unroll 1
     for (int kb = 0; kb < 2; ++kb) {
-      f32x16 s[2];
+      f32x16 s[RB];
       scores(tk, kb, s);
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
+      for (int cb = 0; cb < RB; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int r = 32 * kb + 8 * (i >> 2) + 4 * hi + (i & 3);
-          s[cb][i] = r <= (cb ? vis1 : vis0) ? s[cb][i] : -INFINITY;
+          s[cb][i] = r <= vis[cb] ? s[cb][i] : -INFINITY;
         }
-      float tmax[2];
+      float tmax[RB];
       block_max(s, tmax);
-      const bool grow0 = tmax[0] > m_used[0] + kTau, grow1 = tmax[1] > m_used[1] + kTau;
-      if (__builtin_amdgcn_ballot_w64(grow0 || grow1) != 0) {
+      bool grows[RB], any_grow = false;
+#pragma unroll
+      for (int cb = 0; cb < RB; ++cb) {
+        grows[cb] = tmax[cb] > m_used[cb] + kTau;
+        any_grow |= grows[cb];
+      }
+      if (__builtin_amdgcn_ballot_w64(any_grow) != 0) {
         // The accumulators live in accumulation registers (the MFMAs read and write them there); this is the
         // only other code that touches them, so it goes through explicit moves.
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const bool grow = cb ? grow1 : grow0;
+        for (int cb = 0; cb < RB; ++cb) {
+          const bool grow = grows[cb];
           const float m_new = grow ? tmax[cb] : m_used[cb];
           // (a row that does not move may still be without a maximum: -inf - -inf must not reach the exponential)
           const float alpha = grow ? __builtin_amdgcn_exp2f(m_used[cb] - m_new) : 1.0f;
@@ -862,17 +976,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
           for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              float t;
-              asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
-                           : "+a"(acc[db][cb][i]), "=&v"(t)
-                           : "v"(alpha));
+              if constexpr (RB == 2) {
+                float t;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(acc[db][cb][i]), "=&v"(t)
+                             : "v"(alpha));
+              } else {
+                acc[db][cb][i] *= alpha;
+              }
             }
         }
       }
-      u32x4 pf[2][2];
+      u32x4 pf[RB][2];
       weights(s, pf);
-      u32x2 vh[NPV];
-      static_for<0, NPV>([&](auto r) { vh[r] = read_v(r, tv, kb); });
+      u32x2 vh[NVR];
+      static_for<0, NVR>([&](auto r) { vh[r] = read_v(r, tv, kb); });
       static_for<0, NPV>([&](auto i) { pv_mfma(i, vh, pf); });
     }
   };
@@ -891,7 +1009,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
+      for (int cb = 0; cb < RB; ++cb) {
         char* sp = stg + (cb * 32 + col) * STG + 8 * hi;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -904,9 +1022,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       // (LDS operations of one wavefront complete in order: no barrier between the writes above and these reads,
       // nor between these reads and the next round's writes)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < 2 * RB; ++i) {
         const int rl = 16 * i + lane / 4, ch = lane % 4;
-        const int rr = wave * 64 + rl;
+        const int rr = wave * WR + rl;
         const int t = (int)(((unsigned)rr * g_magic) >> 16), head = rr - t * G;
         const u32x4 v = *(const u32x4*)(stg + rl * STG + ch * 16);
         if (t < nt)
@@ -918,8 +1036,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
 
   // Piece slots in the workspace.  A slot holds, for the 256 rows, the reference maxima, the sums and the
   // unnormalised accumulators of one piece in the order the lanes hold them: thread t's accumulator values
-  // (db, cb, 4 consecutive i) are the 16 bytes at block ((db*2 + cb)*4 + i/4), position t - every store and load of
-  // the workgroup covers 4 KiB contiguous.  Rows are the same in every workgroup (row = 64*wave + 32*cb + col).
+  // (db, cb, 4 consecutive i) are the 16 bytes at block ((db*RB + cb)*4 + i/4), position t - every store and load of
+  // the workgroup covers 4 or 8 KiB contiguous.  Rows are the same in every workgroup (row = 32*RB*wave + 32*cb + col).
   auto slot_of = [&](uint32_t owner, bool head) -> float* {
     return p.ws + (size_t)(2 * owner + (head ? 1u : 0u)) * piece_floats(D);
   };
@@ -935,12 +1053,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     ntok = min(tb, cur.N - tok0);
     const int nfast_item = cur.fastA + cur.fastB;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      const int t = (wave * 64 + cb * 32 + col) / G;
+    for (int cb = 0; cb < RB; ++cb) {
+      const int t = (wave * WR + cb * 32 + col) / G;
       lim[cb] = P + tok0 + min(t, ntok - 1);  // key j is visible iff j <= lim
     }
     // Rows past the last token of the tile are padding; a wavefront whose 64 rows are all padding computes nothing.
-    wave_idle = (wave * 64) / G >= ntok;
+    wave_idle = (wave * WR) / G >= ntok;
     // The tiles after this piece are first asked for by its third-last tile; in a piece of four tiles or more the
     // look-up runs beside the second tile (scalar work next to the matrix pipe) instead of in front of the first.
     int park_at = s1 - s0 >= 4 ? s0 + 1 : s0 - 1;
@@ -949,14 +1067,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
     // Fast tiles of this piece: s0 .. nf-1.
     int nf = min(s1, nfast_item);
     Piece nxt;
-    u32x4 qn[2][KS];
+    u32x4 qn[RB][KS];
     for (int attempt = 0;; ++attempt) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) zero(acc[db][cb]);
-      m_used[0] = m_used[1] = -INFINITY;
-      l_run[0] = l_run[1] = 0.f;
+        for (int cb = 0; cb < RB; ++cb) zero(acc[db][cb]);
+#pragma unroll
+      for (int cb = 0; cb < RB; ++cb) {
+        m_used[cb] = -INFINITY;
+        l_run[cb] = 0.f;
+      }
 
       Tile t2;
       run_end = run_end_of(s0 + 2);
@@ -975,10 +1096,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       // The Q operands stay in accumulation registers (MFMA reads its B operand from there as well), which leaves
       // the vector registers to the scores, the weights and the in-flight LDS operand reads.  They are pinned
       // there only now, so that their loads and the first tiles' loads are in flight together.
+      if constexpr (RB == 2) {
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < RB; ++cb)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
+          for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[cb][ks]));
+      }
       int kt = s0;
       if (wave_idle) {
         // No row of this wavefront belongs to a token (the last token tile of a request is padded to 256 rows): it
@@ -1000,18 +1123,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         u32x4 k0[KS];
         {
           const char* first = buf_of(gt);
-          static_for<0, KS>([&](auto ks) { k0[ks] = read_k(ks, first, 0); });
-          f32x16 s[2];
-          float tmax[2];
-          zero(s[0]);
-          zero(s[1]);
           static_for<0, KS>([&](auto ks) {
-            s[0] = PElem<DT>::mfma(k0[ks], qf[0][ks], s[0]);
-            s[1] = PElem<DT>::mfma(k0[ks], qf[1][ks], s[1]);
+            k_at[ks] = lds_addr_of(first + col * ROWB + (((2 * ks + hi) ^ kswz) * 16));
+            k0[ks] = lds_read16(k_at[ks]);
+          });
+          f32x16 s[RB];
+          float tmax[RB];
+#pragma unroll
+          for (int cb = 0; cb < RB; ++cb) zero(s[cb]);
+          static_for<0, KS>([&](auto ks) {
+#pragma unroll
+            for (int cb = 0; cb < RB; ++cb) s[cb] = PElem<DT>::mfma(k0[ks], qf[cb][ks], s[cb]);
           });
           block_max(s, tmax);
-          m_used[0] = tmax[0] - (DT == VT_F16 ? 8.0f : 0.0f);
-          m_used[1] = tmax[1] - (DT == VT_F16 ? 8.0f : 0.0f);
+#pragma unroll
+          for (int cb = 0; cb < RB; ++cb) m_used[cb] = tmax[cb] - (DT == VT_F16 ? 8.0f : 0.0f);
         }
         for (; kt < nf; ++kt, ++gt) {
           if (kt == park_at) park_ahead();
@@ -1041,17 +1167,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       if (attempt > 0 || nf <= s0) break;
       // Fixed reference maxima can overflow the weights when later scores are far larger than the first ones: then
       // some sum or accumulator is no longer finite and the whole workgroup redoes the piece the classic way.
-      float chk = l_run[0] + l_run[1];
+      float chk = 0.f;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int cb = 0; cb < RB; ++cb) {
+        chk += l_run[cb];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) chk += __builtin_fabsf(acc[db][cb][i]);
+      }
       const bool bad = __builtin_amdgcn_ballot_w64(!(chk < INFINITY)) != 0;
       if (lane == 0) s_vote[wave] = bad ? 1 : 0;
       lds_barrier();
-      const int any_bad = uni(s_vote[0] | s_vote[1] | s_vote[2] | s_vote[3]);
+      int votes = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) votes |= s_vote[w];
+      const int any_bad = uni(votes);
       lds_barrier();  // (nobody writes the votes of the next piece before everybody has read these)
       if (!any_bad) break;
       // Start over from the piece's first tile: nothing may be in flight into the buffers, nobody may still read them.
@@ -1061,7 +1192,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       nf = s0;
     }
 
-    float l_tot[2] = {l_run[0] + __shfl_xor(l_run[0], 32), l_run[1] + __shfl_xor(l_run[1], 32)};
+    float l_tot[RB];
+#pragma unroll
+    for (int cb = 0; cb < RB; ++cb) l_tot[cb] = l_run[cb] + __shfl_xor(l_run[cb], 32);
     bool finish = s0 == 0 && s1 == cur.nkt;  // the piece is the whole item
     if (!finish) {
       // The item is shared with other workgroups.  Its pieces meet in the workspace: whoever finishes a piece adds
@@ -1102,10 +1235,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
         float* sl = slot_of(group, group == w0);
         if (!wave_idle) {
 #pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
+          for (int cb = 0; cb < RB; ++cb) {
             if (hi == 0) {
-              __hip_atomic_store(sl + wave * 64 + cb * 32 + col, m_used[cb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              __hip_atomic_store(sl + 256 + wave * 64 + cb * 32 + col, l_tot[cb], __ATOMIC_RELAXED,
+              __hip_atomic_store(sl + wave * WR + cb * 32 + col, m_used[cb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              __hip_atomic_store(sl + 256 + wave * WR + cb * 32 + col, l_tot[cb], __ATOMIC_RELAXED,
                                  __HIP_MEMORY_SCOPE_AGENT);
             }
 #pragma unroll
@@ -1114,7 +1247,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
               for (int q4 = 0; q4 < 4; ++q4) {
                 const f32x4 w = {acc[db][cb][4 * q4], acc[db][cb][4 * q4 + 1], acc[db][cb][4 * q4 + 2],
                                  acc[db][cb][4 * q4 + 3]};
-                store16_device(sl + 512 + (size_t)(((db * 2 + cb) * 4 + q4) * 256 + tid) * 4, w);
+                store16_device(sl + 512 + (size_t)(((db * RB + cb) * 4 + q4) * NT + tid) * 4, w);
               }
           }
         }
@@ -1142,14 +1275,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
             if (tile_at(sh, c1) <= tile_at(sh, c0)) continue;
             const float* sl = slot_of(u, u == w0);
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-              const int r = wave * 64 + cb * 32 + col;
+            for (int cb = 0; cb < RB; ++cb) {
+              const int r = wave * WR + cb * 32 + col;
               f32x4 o[4 * DB];
 #pragma unroll
               for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4)
-                  load16_device(o[4 * db + q4], sl + 512 + (size_t)(((db * 2 + cb) * 4 + q4) * 256 + tid) * 4);
+                  load16_device(o[4 * db + q4], sl + 512 + (size_t)(((db * RB + cb) * 4 + q4) * NT + tid) * 4);
               const float m_o = __hip_atomic_load(sl + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               const float l_o = __hip_atomic_load(sl + 256 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               static_assert(DB == 4 || DB == 2, "operand list below");
@@ -1186,13 +1319,15 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillParams p) {
       }
     }
     if (finish) {
-      const float inv[2] = {1.0f / l_tot[0], 1.0f / l_tot[1]};
+      float inv[RB];
+#pragma unroll
+      for (int cb = 0; cb < RB; ++cb) inv[cb] = 1.0f / l_tot[cb];
       write_rows(cur, inv);
     }
     if (!nxt.valid) break;
     cur = nxt;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < RB; ++cb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) qf[cb][ks] = qn[cb][ks];
   }  // piece loop
@@ -1304,16 +1439,25 @@ int launch_prefill(vt_ctx* ctx, const vt_prefill_args* a, void* stream) {
   p.arrivals = (unsigned long long*)ctx->arrivals;
   p.launch = ++ctx->prefill_launches;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid(p.n_groups), block(256);
+  // head_dim 128: eight wavefronts of 32 rows (two per SIMD); head_dim 64: four wavefronts of 64 rows.
+  const bool narrow = a->head_dim == 128 && !ctx->prefill_wide;
+  const dim3 grid(p.n_groups), block(narrow ? 512 : 256);
   prof_begin(ctx, 1, st);
-  if (a->dtype == VT_BF16 && a->head_dim == 128)
-    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128>), grid, block, 0, st, p);
-  else if (a->dtype == VT_BF16 && a->head_dim == 64)
-    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 64>), grid, block, 0, st, p);
-  else if (a->dtype == VT_F16 && a->head_dim == 128)
-    hipLaunchKernelGGL((prefill_kernel<VT_F16, 128>), grid, block, 0, st, p);
-  else
-    hipLaunchKernelGGL((prefill_kernel<VT_F16, 64>), grid, block, 0, st, p);
+  if (a->dtype == VT_BF16 && a->head_dim == 128) {
+    if (narrow)
+      hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128, 1>), grid, block, 0, st, p);
+    else
+      hipLaunchKernelGGL((prefill_kernel<VT_BF16, 128, 2>), grid, block, 0, st, p);
+  } else if (a->dtype == VT_BF16 && a->head_dim == 64) {
+    hipLaunchKernelGGL((prefill_kernel<VT_BF16, 64, 2>), grid, block, 0, st, p);
+  } else if (a->dtype == VT_F16 && a->head_dim == 128) {
+    if (narrow)
+      hipLaunchKernelGGL((prefill_kernel<VT_F16, 128, 1>), grid, block, 0, st, p);
+    else
+      hipLaunchKernelGGL((prefill_kernel<VT_F16, 128, 2>), grid, block, 0, st, p);
+  } else {
+    hipLaunchKernelGGL((prefill_kernel<VT_F16, 64, 2>), grid, block, 0, st, p);
+  }
   prof_end(ctx, st);
   return hipGetLastError() == hipSuccess ? VT_OK : VT_E_DRIVER;
 }

@@ -132,6 +132,34 @@ def test_paper_sweep_point_16k_context_ratio_half(ctx):
     check_prefill(ctx, cfg, d, "sweep p1 point")
 
 
+def test_four_wavefront_kernel_at_head_dim_128():
+    """head_dim 128 runs as eight wavefronts of 32 rows; a context created under VT_PREFILL_WIDE=1 runs the
+    four-wavefront kernel (the one head_dim 64 always uses) on the same inputs: edge lengths, a shared item, a
+    dominant late key (the fallback to the classic softmax) and workload 3, each against the oracle."""
+    import os
+    os.environ["VT_PREFILL_WIDE"] = "1"
+    try:
+        wide = vt.vt_init(0, 0, 0)
+    finally:
+        del os.environ["VT_PREFILL_WIDE"]
+    try:
+        plens = [0, 0, 1, 63, 64, 65, 127, 500, 0, 300, 129]
+        nlens = [1, 130, 1, 64, 65, 63, 1, 1, 64, 257, 128]
+        cfg, d = with_lens(CONFIGS[3], plens, nlens)
+        check_prefill(wide, cfg, d, "wide edges")
+        cfg, d = with_lens(CONFIGS[3].replace(dtype="f16", n_q_heads=8, n_kv_heads=8), [5000], [40], seed=77)
+        check_prefill(wide, cfg, d, "wide shared item")
+        cfg, d = with_lens(CONFIGS[3], [300, 200], [70, 130], seed=77)
+        q = oracle.widen(d["q_new"], cfg.dtype) + 0.5
+        d["q_new"] = workloads.gen._round_bits(q.astype(np.float32), cfg.dtype)
+        d["k"][0][250] = workloads.gen._round_bits(np.full((cfg.n_kv_heads, cfg.head_dim), 40.0, np.float32), cfg.dtype)
+        check_prefill(wide, cfg, d, "wide dominant late key")
+        check_prefill(wide, CONFIGS[3], workloads.prefill_inputs(CONFIGS[3]), "wide config3")
+    finally:
+        torch.cuda.synchronize()
+        vt.vt_destroy(wide)
+
+
 def test_one_item_shared_by_many_workgroups(ctx):
     """A single (request, kv head, token tile) with a long prefix: its key tiles are spread over several workgroups
     and the merge kernel combines more than two pieces."""
