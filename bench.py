@@ -324,8 +324,8 @@ class Bench:
         wall_first, kms_first, _ = run(10, True)
         n_warm = int(np.ceil(0.06 / wall_first))
         run(n_warm, False)
-        reps = max(reps, int(np.ceil(0.03 / wall_first)))
-        wall, kms, n = run(reps, True)
+        reps_pf = max(reps, int(np.ceil(0.03 / wall_first)))
+        wall, kms, n = run(reps_pf, True)
         flops = prefill_flops(pl, d["new_lens"], hq, D)
         leg = {"config": cfg_id, "workload": cfg.name, "kind": "prefix-prefill call" + (
                    ", then extend + append of the new turn and one decode step" if then_decode else ""),
@@ -334,7 +334,7 @@ class Bench:
                "dtype": cfg.dtype, "new_tokens": T, "value": round(flops / wall / 1e12, 1), "unit": "TFLOP/s",
                "ms_per_call": round(wall * 1e3, 4), "prefill_tokens_per_s": round(T / wall, 1),
                "work_groups": int(plan.n_groups), "key_tiles": int(plan.n_tiles), "items": int(plan.n_items),
-               "warmup_launches": 10 + n_warm, "timed_launches": reps,
+               "warmup_launches": 10 + n_warm, "timed_launches": reps_pf,
                "kernel_ms_first_10_launches_after_idle": round(kms_first, 4),
                "roofline": roofline_mfma("prefill_kernel", cfg.name, kms, n, flops)}
         got = out.cpu().numpy().view(np.uint16)

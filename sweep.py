@@ -12,9 +12,9 @@ A reporting tool like bench.py, not part of the library.
   p1  prefix-prefill, context 16K, prefix ratio 0.5, batch 1..16        (batch-size sweep; 32/4 and 32/8 heads)
   p2  prefix-prefill, context 16K, batch 4, prefix ratio 0.1..0.9       (prefix-ratio sweep)
   e1  prefix-prefill on N(0,1) data against all-zero data, the first launches on an idle device against the
-      settled speed, with the shader clock read from rocm-smi while the kernel loops: how much of the kernel's
-      time is the chip's power management (the clock drops under random operands) rather than the instruction
-      schedule
+      settled speed, the kernel of eight 32-row wavefronts against the one of four 64-row wavefronts, with the
+      shader clock read from rocm-smi while the kernel loops: how much of the kernel's time is the chip's power
+      management (the clock drops under random operands) rather than the instruction schedule
   m1  memory accounting against the running batch size ("Memory Flexibility"): physical memory mapped by the
       regions while the batch grows to 64 requests and shrinks again, against the virtual range reserved and
       against a static preallocation for the largest batch at the maximum length.  Runs on the host backend
@@ -172,9 +172,15 @@ def clock_experiment(vt, torch, ctx, say):
     c3 = workloads.CONFIGS[3]
     cases = [("workload 3 (B16, P 1K-4K, N 128-512)", c3, 20),
              ("context 16K, prefix ratio 0.5, batch 4", c3.replace(batch=4, kv_len=(8192, 8192), new_len=(8192, 8192)), 5)]
-    say("\n### e1: prefill_kernel, 32/8 heads, bf16: operand data and launch pattern\n")
-    say("| shape | data | first 10 launches on an idle device, us | settled (after 60 ms of launches), us | TFLOP/s | of 2.5 PFLOP/s | sclk after 1 s of launches |")
-    say("|---|---|---|---|---|---|---|")
+    say("\n### e1: prefill_kernel, 32/8 heads, bf16: operand data, launch pattern and kernel shape\n")
+    say("| shape | kernel | data | first 10 launches on an idle device, us | settled (after 60 ms of launches), us | TFLOP/s | of 2.5 PFLOP/s | sclk after 1 s of launches |")
+    say("|---|---|---|---|---|---|---|---|")
+    # the four-wavefront kernel is what a context created under VT_PREFILL_WIDE=1 runs at head_dim 128
+    os.environ["VT_PREFILL_WIDE"] = "1"
+    try:
+        wide = vt.vt_init(0, 0, 0)
+    finally:
+        del os.environ["VT_PREFILL_WIDE"]
     for name, cfg, reps in cases:
         d0 = workloads.prefill_inputs(cfg, threads=16)
         for data in ("N(0,1)", "zeros"):
@@ -184,50 +190,52 @@ def clock_experiment(vt, torch, ctx, say):
                     d[key] = np.zeros_like(d0[key])
                 d["k"] = [np.zeros_like(x) for x in d0["k"]]
                 d["v"] = [np.zeros_like(x) for x in d0["v"]]
-            st = torch.cuda.current_stream().cuda_stream
-            kvs = []
-            for b in range(cfg.batch):
-                kv = vt.vt_reserve(ctx, cfg.n_kv_heads, cfg.head_dim, vt.VT_BF16, int(d["prefix_lens"][b]) + 1)
-                vt.vt_extend(kv, int(d["prefix_lens"][b]))
-                kd = torch.from_numpy(d["k"][b].view(np.int16)).cuda()
-                vd = torch.from_numpy(d["v"][b].view(np.int16)).cuda()
-                vt.vt_append(kv, kd, vd, int(d["prefix_lens"][b]), 0, st)
-                torch.cuda.synchronize()
-                kvs.append(kv)
-            infos = [vt.vt_query(x) for x in kvs]
-            kp = torch.tensor([i.k_ptr for i in infos], dtype=torch.int64).cuda()
-            vp = torch.tensor([i.v_ptr for i in infos], dtype=torch.int64).cuda()
-            dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
-            qn, kn, vn = dev(d["q_new"]), dev(d["k_new"]), dev(d["v_new"])
-            out = torch.zeros_like(qn)
-            cu = np.ascontiguousarray(d["cu_seqlens"], np.int32)
-            pl = np.ascontiguousarray(d["prefix_lens"], np.int32)
-            a = vt.make_prefill_args(vt.VT_BF16, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.scale,
-                                     int(cu[-1]), qn, out, kn, vn, kp, vp, torch.from_numpy(cu).cuda(),
-                                     torch.from_numpy(pl).cuda(), cu, pl)
-            n, p = d["new_lens"].astype(np.int64), pl.astype(np.int64)
-            flops = float(4 * cfg.n_q_heads * cfg.head_dim * np.sum(n * p + n * (n + 1) // 2))
-
-            launch = lambda: vt.vt_attn_prefix_prefill(ctx, a, st)
-            first, busy = _settled_us(vt, torch, ctx, launch, reps)
-            stop = [False]
-
-            def spin():
-                while not stop[0]:
-                    for _ in range(50 if reps > 5 else 5):
-                        vt.vt_attn_prefix_prefill(ctx, a, st)
+            for kernel, c in (("8 wavefronts x 32 rows", ctx), ("4 wavefronts x 64 rows", wide)):
+                st = torch.cuda.current_stream().cuda_stream
+                kvs = []
+                for b in range(cfg.batch):
+                    kv = vt.vt_reserve(c, cfg.n_kv_heads, cfg.head_dim, vt.VT_BF16, int(d["prefix_lens"][b]) + 1)
+                    vt.vt_extend(kv, int(d["prefix_lens"][b]))
+                    kd = torch.from_numpy(d["k"][b].view(np.int16)).cuda()
+                    vd = torch.from_numpy(d["v"][b].view(np.int16)).cuda()
+                    vt.vt_append(kv, kd, vd, int(d["prefix_lens"][b]), 0, st)
                     torch.cuda.synchronize()
-            t = threading.Thread(target=spin)
-            t.start()
-            time.sleep(1.0)
-            clk = _sclk()
-            stop[0] = True
-            t.join()
-            say("| %s | %s | %.1f | %.1f | %.0f | %.3f | %s |" % (name, data, first, busy, flops / busy / 1e6,
-                                                             flops / busy / 1e6 / 2500, clk))
-            torch.cuda.synchronize()
-            for kv in kvs:
-                vt.vt_release(kv)
+                    kvs.append(kv)
+                infos = [vt.vt_query(x) for x in kvs]
+                kp = torch.tensor([i.k_ptr for i in infos], dtype=torch.int64).cuda()
+                vp = torch.tensor([i.v_ptr for i in infos], dtype=torch.int64).cuda()
+                dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+                qn, kn, vn = dev(d["q_new"]), dev(d["k_new"]), dev(d["v_new"])
+                out = torch.zeros_like(qn)
+                cu = np.ascontiguousarray(d["cu_seqlens"], np.int32)
+                pl = np.ascontiguousarray(d["prefix_lens"], np.int32)
+                a = vt.make_prefill_args(vt.VT_BF16, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.scale,
+                                         int(cu[-1]), qn, out, kn, vn, kp, vp, torch.from_numpy(cu).cuda(),
+                                         torch.from_numpy(pl).cuda(), cu, pl)
+                n, p = d["new_lens"].astype(np.int64), pl.astype(np.int64)
+                flops = float(4 * cfg.n_q_heads * cfg.head_dim * np.sum(n * p + n * (n + 1) // 2))
+                launch = lambda: vt.vt_attn_prefix_prefill(c, a, st)
+                first, busy = _settled_us(vt, torch, c, launch, reps)
+                stop = [False]
+
+                def spin():
+                    while not stop[0]:
+                        for _ in range(50 if reps > 5 else 5):
+                            vt.vt_attn_prefix_prefill(c, a, st)
+                        torch.cuda.synchronize()
+                t = threading.Thread(target=spin)
+                t.start()
+                time.sleep(1.0)
+                clk = _sclk()
+                stop[0] = True
+                t.join()
+                say("| %s | %s | %s | %.1f | %.1f | %.0f | %.3f | %s |" % (name, kernel, data, first, busy,
+                                                                      flops / busy / 1e6, flops / busy / 1e6 / 2500, clk))
+                torch.cuda.synchronize()
+                for kv in kvs:
+                    vt.vt_release(kv)
+    torch.cuda.synchronize()
+    vt.vt_destroy(wide)
 
 
 def memory_accounting(vt, say):
