@@ -142,3 +142,21 @@ def test_decode_plan_rule():
     assert meta.decode_plan([5], 8) == (32, [1], 1, 8)
     assert meta.decode_plan([40], 8)[0:2] == (32, [2])
     assert meta.decode_plan([7, 9], 4096)[0] == 32            # more heads than slots: one segment per head
+
+
+def test_traffic_summary_has_a_line_for_every_bench_leg():
+    """bench.py takes the `traffic` field of its roofline objects from profiles/hbm_traffic_per_kernel.md: every
+    workload's line must be there and parse (a measured ratio near 1 for the memory-bound kernel, measured bytes at
+    or above the algorithmic ones for the other)."""
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for cfg_id in (1, 2, 4, 5):
+        ratio = bench.traffic_entry("traffic_ratio", "decode_kernel", CONFIGS[cfg_id].name)
+        assert ratio is not None and 1.0 <= ratio < 1.3, (cfg_id, ratio)
+    for cfg_id in (3, 4):
+        nbytes = bench.traffic_entry("traffic_bytes", "prefill_kernel", CONFIGS[cfg_id].name)
+        lo, hi = CONFIGS[cfg_id].kv_len
+        assert nbytes is not None and nbytes > CONFIGS[cfg_id].batch * lo * 2 * CONFIGS[cfg_id].n_kv_heads * 128 * 2
